@@ -1,0 +1,209 @@
+"""Seeded synthetic inputs and layer-shape recipes.
+
+Serves both the GPU library's callers (tests, bench) and the CPU oracle's
+callers; holds none of the method's arithmetic.  Shapes follow the networks of
+Section IV-A of arXiv 2006.09791 (WRN-40-2 for CIFAR-sized 32x32 inputs,
+ResNet-34 and MobileNet-style depthwise layers for 224x224 inputs); values are
+synthetic: inputs uniform in [-1, 1), weights normal with std sqrt(2 / fan_in),
+fan_in = (Cin/g) * KH * KW.
+"""
+from collections import namedtuple
+
+import numpy as np
+
+# One step of a layer chain.  Buffers are referred to by index.
+#   op    : "conv" | "maxpool" | "add" | "relu"
+#   src   : input buffer; src2: second operand ("add") or residual added to the
+#           convolution result before the optional ReLU ("conv"), -1 if none
+#   relu  : apply max(., 0) to the result of a conv / add
+#   wid   : index into the chain's weight list (conv only)
+Layer = namedtuple(
+    "Layer", "op src src2 dst N Cin H W Cout KH KW stride pad groups relu wid")
+
+ConvShape = namedtuple("ConvShape", "N Cin H W Cout KH KW stride pad groups")
+
+
+def out_size(size, k, stride, pad):
+    return (size + 2 * pad - k) // stride + 1
+
+
+def conv_macs(s):
+    """MAC count of one layer (Eq. 2 of the paper)."""
+    ho, wo = out_size(s.H, s.KH, s.stride, s.pad), out_size(s.W, s.KW, s.stride, s.pad)
+    return s.N * s.Cin * s.Cout * s.KH * s.KW * ho * wo // s.groups
+
+
+def make_seed(config_id, layer_index, groups):
+    return (1000003 * config_id + 1009 * layer_index + groups) % (2 ** 31 - 1)
+
+
+def make_input(shape, seed):
+    rng = np.random.default_rng(seed)
+    return rng.uniform(-1.0, 1.0, size=shape).astype(np.float32)
+
+
+def make_weight(Cout, CPG, KH, KW, seed):
+    rng = np.random.default_rng(seed + 7919)
+    std = np.sqrt(2.0 / (CPG * KH * KW))
+    return (rng.standard_normal(size=(Cout, CPG, KH, KW)) * std).astype(np.float32)
+
+
+def round_to_bf16(a):
+    """fp32 -> nearest-even bf16.  Returns (uint16 bit patterns, the same
+    values widened back to fp32)."""
+    a = np.ascontiguousarray(a, dtype=np.float32)
+    u = a.view(np.uint32).astype(np.uint64)
+    lsb = (u >> 16) & 1
+    r = ((u + 0x7FFF + lsb) >> 16).astype(np.uint16)
+    back = (r.astype(np.uint32) << 16).view(np.float32)
+    return r, back.reshape(a.shape)
+
+
+# ----------------------------------------------------------------------------
+# Single layers
+# ----------------------------------------------------------------------------
+def config1():
+    """Small smoke / parity case: 64 -> 64 channels, 32x32, 3x3, g = 4."""
+    return ConvShape(1, 64, 32, 32, 64, 3, 3, 1, 1, 4)
+
+
+def wrn_grouped_shapes(N, g):
+    """The five distinct grouped 3x3 layers of the WRN-40-2-style stack."""
+    return [
+        ConvShape(N, 32, 32, 32, 32, 3, 3, 1, 1, g),
+        ConvShape(N, 32, 32, 32, 64, 3, 3, 2, 1, g),
+        ConvShape(N, 64, 16, 16, 64, 3, 3, 1, 1, g),
+        ConvShape(N, 64, 16, 16, 128, 3, 3, 2, 1, g),
+        ConvShape(N, 128, 8, 8, 128, 3, 3, 1, 1, g),
+    ]
+
+
+def resnet34_grouped_shapes(N, g):
+    """The seven distinct grouped 3x3 layers of the ResNet-34-shaped stack."""
+    return [
+        ConvShape(N, 64, 56, 56, 64, 3, 3, 1, 1, g),
+        ConvShape(N, 64, 56, 56, 128, 3, 3, 2, 1, g),
+        ConvShape(N, 128, 28, 28, 128, 3, 3, 1, 1, g),
+        ConvShape(N, 128, 28, 28, 256, 3, 3, 2, 1, g),
+        ConvShape(N, 256, 14, 14, 256, 3, 3, 1, 1, g),
+        ConvShape(N, 256, 14, 14, 512, 3, 3, 2, 1, g),
+        ConvShape(N, 512, 7, 7, 512, 3, 3, 1, 1, g),
+    ]
+
+
+DEPTHWISE_CH_HW = [(32, 112), (64, 112), (128, 56), (256, 28), (512, 14), (1024, 7)]
+
+
+def depthwise_pairs(N=1):
+    """MobileNet-shaped (depthwise 3x3, pointwise 1x1 C -> 2C) layer pairs."""
+    pairs = []
+    for C, hw in DEPTHWISE_CH_HW:
+        for stride in (1, 2):
+            dw = ConvShape(N, C, hw, hw, C, 3, 3, stride, 1, C)
+            ho = out_size(hw, 3, stride, 1)
+            pw = ConvShape(N, C, ho, ho, 2 * C, 1, 1, 1, 0, 1)
+            pairs.append((dw, pw))
+    return pairs
+
+
+# ----------------------------------------------------------------------------
+# Layer chains
+# ----------------------------------------------------------------------------
+class Chain:
+    """A list of Layer steps plus the buffers and weights they refer to."""
+
+    def __init__(self, name, input_shape):
+        self.name = name
+        self.input_shape = tuple(input_shape)
+        self.layers = []
+        self.weight_shapes = []      # (Cout, CPG, KH, KW) per conv
+        self.weight_groups = []
+        self.buf_elems = [int(np.prod(input_shape))]   # buffer 0 = chain input
+        self.out_buf = 0
+        self.out_shape = tuple(input_shape)
+
+    def _need(self, buf, elems):
+        while len(self.buf_elems) <= buf:
+            self.buf_elems.append(0)
+        self.buf_elems[buf] = max(self.buf_elems[buf], int(elems))
+
+    def conv(self, src, dst, N, Cin, H, W, Cout, k, stride, pad, groups,
+             relu=False, residual=-1):
+        ho, wo = out_size(H, k, stride, pad), out_size(W, k, stride, pad)
+        wid = len(self.weight_shapes)
+        self.weight_shapes.append((Cout, Cin // groups, k, k))
+        self.weight_groups.append(groups)
+        self.layers.append(Layer("conv", src, residual, dst, N, Cin, H, W, Cout,
+                                 k, k, stride, pad, groups, bool(relu), wid))
+        self._need(dst, N * Cout * ho * wo)
+        self.out_buf, self.out_shape = dst, (N, Cout, ho, wo)
+        return ho, wo
+
+    def maxpool(self, src, dst, N, C, H, W, k=3, stride=2, pad=1):
+        ho, wo = out_size(H, k, stride, pad), out_size(W, k, stride, pad)
+        self.layers.append(Layer("maxpool", src, -1, dst, N, C, H, W, C, k, k,
+                                 stride, pad, 1, False, -1))
+        self._need(dst, N * C * ho * wo)
+        self.out_buf, self.out_shape = dst, (N, C, ho, wo)
+        return ho, wo
+
+    def macs(self):
+        return sum(conv_macs(ConvShape(l.N, l.Cin, l.H, l.W, l.Cout, l.KH, l.KW,
+                                       l.stride, l.pad, l.groups))
+                   for l in self.layers if l.op == "conv")
+
+    def make_weights(self, config_id):
+        return [make_weight(*shp, seed=make_seed(config_id, i, g))
+                for i, (shp, g) in enumerate(zip(self.weight_shapes,
+                                                 self.weight_groups))]
+
+
+def _basic_stage(ch, cur, N, cin, cout, hw, blocks, g, entry_stride):
+    """Residual stage of basic blocks (two grouped 3x3 convs each).  Buffers
+    1..4 rotate; `cur` holds the stage input.  Returns (buffer, spatial)."""
+    for b in range(blocks):
+        free = [i for i in (1, 2, 3, 4) if i != cur]
+        t, sc, out = free[0], free[1], free[2]
+        if b == 0 and (entry_stride != 1 or cin != cout):
+            ho, _ = ch.conv(cur, sc, N, cin, hw, hw, cout, 1, entry_stride, 0, 1)
+            ch.conv(cur, t, N, cin, hw, hw, cout, 3, entry_stride, 1, g, relu=True)
+            ch.conv(t, out, N, cout, ho, ho, cout, 3, 1, 1, g, relu=True, residual=sc)
+            hw = ho
+        else:
+            ch.conv(cur, t, N, cout, hw, hw, cout, 3, 1, 1, g, relu=True)
+            ch.conv(t, out, N, cout, hw, hw, cout, 3, 1, 1, g, relu=True, residual=cur)
+        cur = out
+    return cur, hw
+
+
+def wrn_chain(N, g):
+    """WRN-40-2-style CIFAR stack, every 3x3 conv after the stem grouped."""
+    ch = Chain(f"wrn40x2_g{g}_n{N}", (N, 3, 32, 32))
+    ch.conv(0, 1, N, 3, 32, 32, 32, 3, 1, 1, 1, relu=True)
+    cur, hw = 1, 32
+    cur, hw = _basic_stage(ch, cur, N, 32, 32, hw, 6, g, 1)
+    cur, hw = _basic_stage(ch, cur, N, 32, 64, hw, 6, g, 2)
+    cur, hw = _basic_stage(ch, cur, N, 64, 128, hw, 6, g, 2)
+    return ch
+
+
+def resnet34_chain(N, g):
+    """ResNet-34-shaped ImageNet stack: 7x7 s2 stem, 3x3 s2 max pool, then
+    3/4/6/3 basic blocks with every 3x3 conv grouped."""
+    ch = Chain(f"resnet34_g{g}_n{N}", (N, 3, 224, 224))
+    ho, _ = ch.conv(0, 1, N, 3, 224, 224, 64, 7, 2, 3, 1, relu=True)
+    ho, _ = ch.maxpool(1, 2, N, 64, ho, ho)
+    cur, hw = 2, ho
+    cur, hw = _basic_stage(ch, cur, N, 64, 64, hw, 3, g, 1)
+    cur, hw = _basic_stage(ch, cur, N, 64, 128, hw, 4, g, 2)
+    cur, hw = _basic_stage(ch, cur, N, 128, 256, hw, 6, g, 2)
+    cur, hw = _basic_stage(ch, cur, N, 256, 512, hw, 3, g, 2)
+    return ch
+
+
+def mobilenet_dw_chain(N, C, hw, stride):
+    """Depthwise 3x3 (g = C) followed by a pointwise 1x1 C -> 2C."""
+    ch = Chain(f"dw_c{C}_hw{hw}_s{stride}_n{N}", (N, C, hw, hw))
+    ho, _ = ch.conv(0, 1, N, C, hw, hw, C, 3, stride, 1, C, relu=True)
+    ch.conv(1, 2, N, C, ho, ho, 2 * C, 1, 1, 0, 1, relu=True)
+    return ch
