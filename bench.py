@@ -1,0 +1,208 @@
+#!/usr/bin/env python3
+"""Benchmark of the grouped-convolution hot path on one MI355X.
+
+A step is one forward pass of the WRN-40-2-style CIFAR stack (every 3x3 conv
+after the stem grouped, fp32, batch 64) for each g in {1, 2, 4, 8, 16}: five
+layer chains, 195 convolution launches, run through gspc_run_layer_chain with
+all tensors resident in HBM.  `value` is the Eq. 2 MAC count of the step
+divided by its time.  Prints ONE JSON line.
+
+Also reported on the same line:
+  roofline     - for the kernel that takes the largest share of the step: its
+                 algorithmic flops (or bytes) per launch over its average
+                 launch duration, measured here with events on the launch
+                 stream by running each of its layers back to back.
+  cpu_baseline - the CPU oracle timed on the host cores on a bounded sample.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+GROUPS = (1, 2, 4, 8, 16)
+BATCH = 64
+PEAK_F32_MFMA_TFLOPS = 157.3
+PEAK_HBM_GBS = 8000.0
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "traffic.json")
+
+
+def layer_flops_bytes(l):
+    from paper_2006_09791_amd import workloads as wl
+    ho, wo = wl.out_size(l.H, l.KH, l.stride, l.pad), wl.out_size(l.W, l.KW, l.stride, l.pad)
+    macs = l.N * l.Cin * l.Cout * l.KH * l.KW * ho * wo // l.groups
+    out_b = l.N * l.Cout * ho * wo * 4
+    nbytes = l.N * l.Cin * l.H * l.W * 4 + l.Cout * (l.Cin // l.groups) * l.KH * l.KW * 4 + out_b
+    if l.src2 >= 0:
+        nbytes += out_b          # fused residual read
+    return 2 * macs, nbytes
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-roofline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on exactly one GPU (--gpus 1); "
+              "no multi-GPU path exists", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    from paper_2006_09791_amd import binding as b
+    from paper_2006_09791_amd import workloads as wl
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    dev = torch.device("cuda:0")
+    b.load()                       # raises if libgspc.so is missing: no fallback
+    b.gspc_set_stream()
+
+    # ---- build the five chains, everything resident on the device ----------
+    chains, lcs, keep = [], [], []
+    for g in GROUPS:
+        ch = wl.wrn_chain(BATCH, g)
+        weights = ch.make_weights(2)
+        packed = [b.gspc_pack_weights(torch.from_numpy(w).to(dev), gg)
+                  for w, gg in zip(weights, ch.weight_groups)]
+        bufs = [torch.empty(max(n, 1), dtype=torch.float32, device=dev) for n in ch.buf_elems]
+        x0 = wl.make_input(ch.input_shape, wl.make_seed(2, 999, g))
+        bufs[0].copy_(torch.from_numpy(x0).reshape(-1))
+        chains.append(ch)
+        lcs.append(b.LayerChain(ch.layers, packed, bufs))
+        keep.append((packed, bufs))
+    macs_step = sum(ch.macs() for ch in chains)
+
+    def step():
+        for lc in lcs:
+            b.gspc_run_layer_chain(lc)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    sec = t1 - t0
+    ms_per_step = sec / args.steps * 1e3
+    value = macs_step * args.steps / sec / 1e9
+
+    # ---- per-g latency (outside the timed region) --------------------------
+    per_g = {}
+    for g, ch, lc in zip(GROUPS, chains, lcs):
+        reps = max(5, min(50, args.steps))
+        torch.cuda.synchronize()
+        ta = time.perf_counter()
+        for _ in range(reps):
+            b.gspc_run_layer_chain(lc)
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - ta) / reps * 1e3
+        per_g[str(g)] = {"ms": round(ms, 4), "gmacs": round(ch.macs() / ms / 1e6, 1)}
+
+    # ---- roofline of the dominant kernel ------------------------------------
+    roofline = None
+    kernels = {}
+    if not args.no_roofline:
+        reps = 20
+        for ch, (packed, bufs) in zip(chains, keep):
+            seen = {}
+            for l in ch.layers:
+                if l.op != "conv":
+                    continue
+                key = (l.Cin, l.H, l.W, l.Cout, l.KH, l.stride, l.groups, l.src2 >= 0, l.relu)
+                if key in seen:
+                    seen[key][1] += 1
+                    continue
+                seen[key] = [l, 1]
+            for l, count in seen.values():
+                one = b.LayerChain([l], packed, bufs)
+                b.gspc_run_layer_chain(one)
+                name = b.gspc_last_kernel()
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                torch.cuda.synchronize()
+                e0.record()
+                for _ in range(reps):
+                    b.gspc_run_layer_chain(one)
+                e1.record()
+                torch.cuda.synchronize()
+                dur = e0.elapsed_time(e1) / reps * 1e-3
+                flops, nbytes = layer_flops_bytes(l)
+                k = kernels.setdefault(name, {"time": 0.0, "flops": 0.0, "bytes": 0.0, "launches": 0,
+                                              "compute_bound": False})
+                k["time"] += dur * count
+                k["flops"] += flops * count
+                k["bytes"] += nbytes * count
+                k["launches"] += count
+                # fp32 ridge of this GPU: 157.3 TFLOP/s / 8 TB/s = 19.7 flop/B
+                if flops / nbytes > PEAK_F32_MFMA_TFLOPS * 1e3 / PEAK_HBM_GBS:
+                    k["compute_bound"] = True
+        name, k = max(kernels.items(), key=lambda kv: kv[1]["time"])
+        traffic = None
+        if os.path.exists(TRAFFIC_FILE):
+            try:
+                traffic = json.load(open(TRAFFIC_FILE)).get(name)
+            except Exception:
+                traffic = None
+        if "mfma" in name and k["compute_bound"]:
+            ach = k["flops"] / k["time"] / 1e12
+            roofline = {"bound": "mfma", "achieved": round(ach, 2), "peak": PEAK_F32_MFMA_TFLOPS,
+                        "unit": "TFLOP/s", "frac": round(ach / PEAK_F32_MFMA_TFLOPS, 4)}
+        else:
+            ach = k["bytes"] / k["time"] / 1e9
+            roofline = {"bound": "hbm", "achieved": round(ach, 1), "peak": PEAK_HBM_GBS,
+                        "unit": "GB/s", "frac": round(ach / PEAK_HBM_GBS, 4)}
+        roofline.update({"traffic": traffic, "kernel": name, "launches_per_step": k["launches"],
+                         "avg_launch_us": round(k["time"] / k["launches"] * 1e6, 2),
+                         "share_of_step": round(k["time"] / sum(v["time"] for v in kernels.values()), 3)})
+
+    # ---- CPU oracle on a bounded sample -------------------------------------
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+        cores = len(os.sched_getaffinity(0)) if hasattr(os, "sched_getaffinity") else os.cpu_count()
+        cores = max(1, min(cores, oracle.max_threads(), 16))
+        n_s = 32
+        total, t_cpu = 0, 0.0
+        for g in GROUPS:
+            ch = wl.wrn_chain(n_s, g)
+            weights = ch.make_weights(2)
+            x0 = wl.make_input(ch.input_shape, wl.make_seed(2, 999, g))
+            ta = time.perf_counter()
+            oracle.run_chain(ch.layers, len(ch.buf_elems), x0, weights, threads=cores)
+            t_cpu += time.perf_counter() - ta
+            total += ch.macs()
+        cpu = {"value": round(total / t_cpu / 1e9, 3), "unit": "GMAC/s", "cores": cores,
+               "kind": "oracle",
+               "sample": f"same WRN-40-2-style stacks, g in {list(GROUPS)}, batch {n_s} instead of "
+                         f"{BATCH} ({total / 1e9:.2f} GMAC, {t_cpu:.1f} s wall)"}
+
+    out = {
+        "metric": "grouped conv2d GMAC/s (Eq. 2 MACs / time), WRN-40-2-style stack swept over g",
+        "value": round(value, 1), "unit": "GMAC/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "WRN-40-2-style CIFAR stack, 3x32x32 input, every 3x3 conv grouped, "
+                               "fp32, N=64, one pass per g in {1,2,4,8,16} per step",
+                   "batch": BATCH, "groups": list(GROUPS), "gmac_per_step": round(macs_step / 1e9, 3)},
+        "per_g": per_g,
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -230,3 +230,32 @@ def maxpool2d(x, k=3, stride=2, pad=1):
     rc = _load().oracle_maxpool2d(_p(x), N, C, H, W, k, stride, pad, _p(y))
     _check(rc, "maxpool2d")
     return y
+
+
+def run_chain(layers, n_bufs, x0, weights, threads=1):
+    """Executes a list of layer steps (objects with fields op, src, src2, dst,
+    KH, stride, pad, groups, relu, wid) in float64.  A conv step adds buffer
+    src2 (if >= 0) to its result and then applies the optional ReLU, like the
+    residual blocks of the networks of Section IV-A.  Returns all buffers."""
+    bufs = [None] * n_bufs
+    bufs[0] = _f64(x0)
+    for l in layers:
+        if l.op == "conv":
+            y = conv2d_grouped(bufs[l.src], weights[l.wid], l.stride, l.pad, l.groups,
+                               threads=threads)
+            if l.src2 >= 0:
+                y = add(y, bufs[l.src2])
+            if l.relu:
+                y = relu(y)
+        elif l.op == "maxpool":
+            y = maxpool2d(bufs[l.src], l.KH, l.stride, l.pad)
+        elif l.op == "add":
+            y = add(bufs[l.src], bufs[l.src2])
+            if l.relu:
+                y = relu(y)
+        elif l.op == "relu":
+            y = relu(bufs[l.src])
+        else:
+            raise ValueError(f"unknown op {l.op}")
+        bufs[l.dst] = y
+    return bufs

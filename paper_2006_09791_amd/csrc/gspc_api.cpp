@@ -1,0 +1,388 @@
+// Host side of libgspc: argument validation, kernel-family dispatch and the
+// layer-chain runner.  All arithmetic happens in the HIP kernels.
+#include <cstdarg>
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "gspc_internal.h"
+
+namespace {
+
+thread_local hipStream_t t_stream = nullptr;
+thread_local char t_error[512] = "";
+thread_local int t_force_path = GSPC_PATH_AUTO;
+thread_local int t_last_path = GSPC_PATH_AUTO;
+thread_local const char *t_last_kernel = "";
+
+int fail(int code, const char *fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(t_error, sizeof(t_error), fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+int hip_fail(hipError_t e, const char *what) {
+    return fail(GSPC_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
+}
+
+int out_dim(int in, int k, int stride, int pad) {
+    long span = (long)in + 2L * pad - k;
+    if (span < 0) return 0;
+    return (int)(span / stride) + 1;
+}
+
+// Shared validation of a layer's shape arguments.
+int check_shape(int Cin, int Cout, int KH, int KW, int groups) {
+    if (Cin <= 0 || Cout <= 0 || KH <= 0 || KW <= 0)
+        return fail(GSPC_ERR_DIM, "non-positive dimension (Cin=%d Cout=%d KH=%d KW=%d)",
+                    Cin, Cout, KH, KW);
+    if (groups <= 0 || Cin % groups || Cout % groups)
+        return fail(GSPC_ERR_GROUPS, "Cin=%d and Cout=%d must be divisible by groups=%d",
+                    Cin, Cout, groups);
+    return GSPC_OK;
+}
+
+bool valid_handle(const gspc_packed_t *h) {
+    return h && h->magic == gspc::kPackedMagic && h->version == gspc::kVersion;
+}
+
+// Validates a convolution call and fills the kernel parameters.
+int prepare_conv(const void *input, const gspc_packed_t *pw, int N, int Cin, int H,
+                 int W, int Cout, int KH, int KW, int stride, int pad, int groups,
+                 void *output, gspc::ConvParams *p) {
+    if (!input || !pw || !output) return fail(GSPC_ERR_NULL, "null pointer argument");
+    if (!valid_handle(pw)) return fail(GSPC_ERR_MISMATCH, "not a packed-weight handle of this library version");
+    if (N <= 0 || H <= 0 || W <= 0 || stride <= 0 || pad < 0)
+        return fail(GSPC_ERR_DIM, "non-positive dimension (N=%d H=%d W=%d stride=%d pad=%d)",
+                    N, H, W, stride, pad);
+    int rc = check_shape(Cin, Cout, KH, KW, groups);
+    if (rc) return rc;
+    if (pw->Cin != Cin || pw->Cout != Cout || pw->KH != KH || pw->KW != KW ||
+        pw->groups != groups)
+        return fail(GSPC_ERR_MISMATCH,
+                    "handle packed for (Cin=%d Cout=%d KH=%d KW=%d g=%d), called with "
+                    "(Cin=%d Cout=%d KH=%d KW=%d g=%d)",
+                    pw->Cin, pw->Cout, pw->KH, pw->KW, pw->groups, Cin, Cout, KH, KW, groups);
+    const int Hout = out_dim(H, KH, stride, pad), Wout = out_dim(W, KW, stride, pad);
+    if (Hout <= 0 || Wout <= 0)
+        return fail(GSPC_ERR_DIM, "kernel %dx%d does not fit the padded %dx%d input", KH, KW,
+                    H + 2 * pad, W + 2 * pad);
+    const double in_elems = (double)N * Cin * H * W, out_elems = (double)N * Cout * Hout * Wout;
+    if (in_elems >= 2147483648.0 || out_elems >= 2147483648.0)
+        return fail(GSPC_ERR_DIM, "tensor with 2^31 or more elements is not supported");
+    p->x = input;
+    p->wd = reinterpret_cast<const float *>(pw->dev);
+    p->wm = pw->geom.variant != gspc::kMfmaNone
+                ? reinterpret_cast<const float *>(static_cast<const char *>(pw->dev) +
+                                                  pw->geom.mfma_offset)
+                : nullptr;
+    p->y = static_cast<float *>(output);
+    p->res = nullptr;
+    p->N = N; p->Cin = Cin; p->H = H; p->W = W; p->Cout = Cout; p->KH = KH; p->KW = KW;
+    p->stride = stride; p->pad = pad; p->groups = groups;
+    p->CPG = Cin / groups; p->KPG = Cout / groups; p->Hout = Hout; p->Wout = Wout;
+    p->KPGd = pw->geom.KPGd;
+    p->relu = 0;
+    p->in_bf16 = pw->dtype == GSPC_BF16;
+    return GSPC_OK;
+}
+
+// Picks the kernel family and launches.
+int dispatch_conv(const gspc::ConvParams &p, const gspc_packed_t *pw) {
+    const bool can_mfma = gspc::mfma_supported(p, pw->geom);
+    int path = t_force_path;
+    if (path == GSPC_PATH_AUTO) path = can_mfma ? GSPC_PATH_MFMA : GSPC_PATH_DIRECT;
+    if (path == GSPC_PATH_MFMA && !can_mfma)
+        return fail(GSPC_ERR_ARG, "matrix-core path forced but not available for this layer");
+    const char *name = "";
+    hipError_t e = path == GSPC_PATH_MFMA ? gspc::launch_mfma(p, pw->geom, t_stream, &name)
+                                          : gspc::launch_direct(p, t_stream, &name);
+    if (e != hipSuccess) return hip_fail(e, "convolution launch");
+    t_last_path = path;
+    t_last_kernel = name;
+    return GSPC_OK;
+}
+
+}  // namespace
+
+namespace gspc {
+
+PackGeom make_pack_geom(int Cin, int Cout, int KH, int KW, int groups, int /*dtype*/) {
+    PackGeom g{};
+    g.CPG = Cin / groups;
+    g.KPG = Cout / groups;
+    g.Kred = g.CPG * KH * KW;
+    g.KPGd = round_up(g.KPG, 4);
+    g.direct_bytes = (size_t)groups * g.Kred * g.KPGd * sizeof(float);
+    if (g.KPG % 32 == 0) g.variant = kMfma32;
+    else if (g.KPG % 16 == 0) g.variant = kMfma16;
+    else if (g.KPG % 4 == 0) g.variant = kMfma4;
+    else g.variant = kMfmaNone;
+    if (g.variant != kMfmaNone) {
+        g.ksub = mfma_ksub(g.variant);
+        g.CPGp = round_up(g.CPG, g.ksub);
+        g.ksteps = g.CPGp / g.ksub * KH * KW;
+        g.mtiles = g.KPG / g.variant;
+        g.mfma_bytes = (size_t)groups * g.mtiles * g.ksteps * 64 * sizeof(float);
+    }
+    g.mfma_offset = (g.direct_bytes + 255) / 256 * 256;
+    g.total_bytes = g.mfma_offset + g.mfma_bytes;
+    return g;
+}
+
+}  // namespace gspc
+
+extern "C" {
+
+int gspc_version(void) { return gspc::kVersion; }
+
+int gspc_set_stream(void *hip_stream) {
+    t_stream = static_cast<hipStream_t>(hip_stream);
+    return GSPC_OK;
+}
+
+const char *gspc_last_error(void) { return t_error; }
+
+int gspc_output_dims(int H, int W, int KH, int KW, int stride, int pad, int *Hout,
+                     int *Wout) {
+    if (!Hout || !Wout) return fail(GSPC_ERR_NULL, "null output pointer");
+    if (H <= 0 || W <= 0 || KH <= 0 || KW <= 0 || stride <= 0 || pad < 0)
+        return fail(GSPC_ERR_DIM, "non-positive dimension");
+    const int ho = out_dim(H, KH, stride, pad), wo = out_dim(W, KW, stride, pad);
+    if (ho <= 0 || wo <= 0) return fail(GSPC_ERR_DIM, "window does not fit the padded input");
+    *Hout = ho;
+    *Wout = wo;
+    return GSPC_OK;
+}
+
+uint64_t gspc_layer_macs(int N, int Cin, int Cout, int KH, int KW, int Hout, int Wout,
+                         int groups) {
+    if (N <= 0 || Cin <= 0 || Cout <= 0 || KH <= 0 || KW <= 0 || Hout <= 0 || Wout <= 0 ||
+        groups <= 0)
+        return 0;
+    return (uint64_t)N * Cin * Cout * KH * KW * Hout * Wout / (uint64_t)groups;
+}
+
+size_t gspc_packed_weight_bytes(int Cin, int Cout, int KH, int KW, int groups, int dtype) {
+    if (check_shape(Cin, Cout, KH, KW, groups)) return 0;
+    if (dtype != GSPC_F32 && dtype != GSPC_BF16) {
+        fail(GSPC_ERR_DTYPE, "unknown dtype %d", dtype);
+        return 0;
+    }
+    return gspc::make_pack_geom(Cin, Cout, KH, KW, groups, dtype).total_bytes;
+}
+
+int gspc_pack_weights(const void *weight_dev, int Cin, int Cout, int KH, int KW, int groups,
+                      int dtype, void *packed_dev, size_t packed_bytes, gspc_packed_t **out) {
+    if (!weight_dev || !packed_dev || !out) return fail(GSPC_ERR_NULL, "null pointer argument");
+    int rc = check_shape(Cin, Cout, KH, KW, groups);
+    if (rc) return rc;
+    if (dtype != GSPC_F32 && dtype != GSPC_BF16) return fail(GSPC_ERR_DTYPE, "unknown dtype %d", dtype);
+    if ((double)Cout * (Cin / groups) * KH * KW >= 2147483648.0)
+        return fail(GSPC_ERR_DIM, "weight tensor with 2^31 or more elements is not supported");
+    const gspc::PackGeom g = gspc::make_pack_geom(Cin, Cout, KH, KW, groups, dtype);
+    if (packed_bytes < g.total_bytes)
+        return fail(GSPC_ERR_SPACE, "packed buffer holds %zu bytes, %zu needed", packed_bytes,
+                    g.total_bytes);
+    if (reinterpret_cast<uintptr_t>(packed_dev) % 256)
+        return fail(GSPC_ERR_ARG, "packed buffer must be 256-byte aligned");
+    gspc_packed_t *h = new (std::nothrow) gspc_packed_t;
+    if (!h) return fail(GSPC_ERR_SPACE, "out of host memory");
+    h->magic = gspc::kPackedMagic;
+    h->version = gspc::kVersion;
+    h->Cin = Cin; h->Cout = Cout; h->KH = KH; h->KW = KW; h->groups = groups; h->dtype = dtype;
+    h->geom = g;
+    h->dev = packed_dev;
+    h->bytes = g.total_bytes;
+    hipError_t e = gspc::launch_pack_weights(static_cast<const float *>(weight_dev), h, t_stream);
+    if (e != hipSuccess) {
+        delete h;
+        return hip_fail(e, "weight pack launch");
+    }
+    *out = h;
+    return GSPC_OK;
+}
+
+int gspc_unpack_weights(const gspc_packed_t *packed, int which, void *weight_dev) {
+    if (!packed || !weight_dev) return fail(GSPC_ERR_NULL, "null pointer argument");
+    if (!valid_handle(packed)) return fail(GSPC_ERR_MISMATCH, "not a packed-weight handle");
+    if (which != GSPC_PATH_DIRECT && which != GSPC_PATH_MFMA)
+        return fail(GSPC_ERR_ARG, "which must be GSPC_PATH_DIRECT or GSPC_PATH_MFMA");
+    if (which == GSPC_PATH_MFMA && packed->geom.variant == gspc::kMfmaNone)
+        return fail(GSPC_ERR_ARG, "handle holds no matrix-core section");
+    hipError_t e = gspc::launch_unpack_weights(packed, which, static_cast<float *>(weight_dev), t_stream);
+    if (e != hipSuccess) return hip_fail(e, "weight unpack launch");
+    return GSPC_OK;
+}
+
+void gspc_packed_free(gspc_packed_t *packed) {
+    if (!packed) return;
+    packed->magic = 0;
+    delete packed;
+}
+
+int gspc_packed_info(const gspc_packed_t *packed, int *Cin, int *Cout, int *KH, int *KW,
+                     int *groups, int *dtype, int *has_mfma) {
+    if (!packed) return fail(GSPC_ERR_NULL, "null handle");
+    if (!valid_handle(packed)) return fail(GSPC_ERR_MISMATCH, "not a packed-weight handle");
+    if (Cin) *Cin = packed->Cin;
+    if (Cout) *Cout = packed->Cout;
+    if (KH) *KH = packed->KH;
+    if (KW) *KW = packed->KW;
+    if (groups) *groups = packed->groups;
+    if (dtype) *dtype = packed->dtype;
+    if (has_mfma) *has_mfma = packed->geom.variant != gspc::kMfmaNone;
+    return GSPC_OK;
+}
+
+int gspc_pack_input_bf16(const void *in_dev, size_t count, void *out_dev) {
+    if (!in_dev || !out_dev) return fail(GSPC_ERR_NULL, "null pointer argument");
+    if (count == 0) return GSPC_OK;
+    hipError_t e = gspc::launch_cast_bf16(static_cast<const float *>(in_dev), count,
+                                          static_cast<uint16_t *>(out_dev), t_stream);
+    if (e != hipSuccess) return hip_fail(e, "bf16 cast launch");
+    return GSPC_OK;
+}
+
+int gspc_conv2d_grouped(const void *input, const gspc_packed_t *packed_weight, int N, int Cin,
+                        int H, int W, int Cout, int KH, int KW, int stride, int pad, int groups,
+                        void *output) {
+    gspc::ConvParams p;
+    int rc = prepare_conv(input, packed_weight, N, Cin, H, W, Cout, KH, KW, stride, pad, groups,
+                          output, &p);
+    if (rc) return rc;
+    return dispatch_conv(p, packed_weight);
+}
+
+int gspc_force_path(int path) {
+    if (path != GSPC_PATH_AUTO && path != GSPC_PATH_DIRECT && path != GSPC_PATH_MFMA)
+        return fail(GSPC_ERR_ARG, "unknown path %d", path);
+    t_force_path = path;
+    return GSPC_OK;
+}
+
+int gspc_last_path(void) { return t_last_path; }
+const char *gspc_last_kernel(void) { return t_last_kernel; }
+
+int gspc_run_layer_chain(const gspc_layer_t *layers, int n_layers, void *const *act_bufs,
+                         const size_t *act_bytes, int n_bufs, float *per_layer_ms) {
+    if (!layers || !act_bufs || !act_bytes) return fail(GSPC_ERR_NULL, "null pointer argument");
+    if (n_layers <= 0 || n_bufs <= 0) return fail(GSPC_ERR_ARG, "empty chain or buffer table");
+    for (int b = 0; b < n_bufs; ++b)
+        if (!act_bufs[b] && act_bytes[b]) return fail(GSPC_ERR_NULL, "activation buffer %d is null", b);
+
+    // Pass 1: validate every step before anything is launched.
+    std::vector<gspc::ConvParams> params(n_layers);
+    for (int i = 0; i < n_layers; ++i) {
+        const gspc_layer_t &L = layers[i];
+        auto buf_ok = [&](int idx) { return idx >= 0 && idx < n_bufs; };
+        if (!buf_ok(L.src) || !buf_ok(L.dst))
+            return fail(GSPC_ERR_ARG, "layer %d: buffer index out of range", i);
+        if (L.N <= 0 || L.Cin <= 0 || L.H <= 0 || L.W <= 0)
+            return fail(GSPC_ERR_DIM, "layer %d: non-positive dimension", i);
+        const double in_elems = (double)L.N * L.Cin * L.H * L.W;
+        if (in_elems >= 2147483648.0) return fail(GSPC_ERR_DIM, "layer %d: tensor too large", i);
+        switch (L.op) {
+        case GSPC_OP_CONV: {
+            if (!L.w) return fail(GSPC_ERR_NULL, "layer %d: conv without weights", i);
+            if (L.dst == L.src || L.dst == L.src2)
+                return fail(GSPC_ERR_ARG, "layer %d: conv output aliases an input", i);
+            int rc = prepare_conv(act_bufs[L.src], L.w, L.N, L.Cin, L.H, L.W, L.Cout, L.KH, L.KW,
+                                  L.stride, L.pad, L.groups, act_bufs[L.dst], &params[i]);
+            if (rc) return rc;
+            gspc::ConvParams &p = params[i];
+            const size_t in_b = (size_t)in_elems * (p.in_bf16 ? 2 : 4);
+            const size_t out_b = (size_t)L.N * L.Cout * p.Hout * p.Wout * 4;
+            if (act_bytes[L.src] < in_b || act_bytes[L.dst] < out_b)
+                return fail(GSPC_ERR_SPACE, "layer %d: activation buffer too small", i);
+            if (L.src2 >= 0) {
+                if (!buf_ok(L.src2)) return fail(GSPC_ERR_ARG, "layer %d: residual index out of range", i);
+                if (act_bytes[L.src2] < out_b)
+                    return fail(GSPC_ERR_SPACE, "layer %d: residual buffer too small", i);
+                p.res = static_cast<const float *>(act_bufs[L.src2]);
+            }
+            p.relu = (L.flags & GSPC_FLAG_RELU) ? 1 : 0;
+            break;
+        }
+        case GSPC_OP_MAXPOOL: {
+            if (L.KH <= 0 || L.KH != L.KW || L.stride <= 0 || L.pad < 0 || 2 * L.pad > L.KH)
+                return fail(GSPC_ERR_DIM, "layer %d: bad pooling window", i);
+            const int ho = out_dim(L.H, L.KH, L.stride, L.pad), wo = out_dim(L.W, L.KW, L.stride, L.pad);
+            if (ho <= 0 || wo <= 0) return fail(GSPC_ERR_DIM, "layer %d: pooling window does not fit", i);
+            if (L.dst == L.src) return fail(GSPC_ERR_ARG, "layer %d: pooling in place", i);
+            if (act_bytes[L.src] < (size_t)in_elems * 4 ||
+                act_bytes[L.dst] < (size_t)L.N * L.Cin * ho * wo * 4)
+                return fail(GSPC_ERR_SPACE, "layer %d: activation buffer too small", i);
+            break;
+        }
+        case GSPC_OP_ADD:
+            if (!buf_ok(L.src2)) return fail(GSPC_ERR_ARG, "layer %d: second operand index out of range", i);
+            if (act_bytes[L.src2] < (size_t)in_elems * 4)
+                return fail(GSPC_ERR_SPACE, "layer %d: activation buffer too small", i);
+            // fallthrough
+        case GSPC_OP_RELU:
+            if (act_bytes[L.src] < (size_t)in_elems * 4 || act_bytes[L.dst] < (size_t)in_elems * 4)
+                return fail(GSPC_ERR_SPACE, "layer %d: activation buffer too small", i);
+            break;
+        default:
+            return fail(GSPC_ERR_ARG, "layer %d: unknown op %d", i, L.op);
+        }
+    }
+
+    // Pass 2: launch.
+    std::vector<hipEvent_t> ev;
+    if (per_layer_ms) {
+        ev.resize(n_layers + 1);
+        for (auto &e : ev) {
+            hipError_t er = hipEventCreate(&e);
+            if (er != hipSuccess) return hip_fail(er, "hipEventCreate");
+        }
+        (void)hipEventRecord(ev[0], t_stream);
+    }
+    int rc = GSPC_OK;
+    for (int i = 0; i < n_layers && rc == GSPC_OK; ++i) {
+        const gspc_layer_t &L = layers[i];
+        const size_t elems = (size_t)L.N * L.Cin * L.H * L.W;
+        hipError_t e = hipSuccess;
+        switch (L.op) {
+        case GSPC_OP_CONV:
+            rc = dispatch_conv(params[i], L.w);
+            break;
+        case GSPC_OP_MAXPOOL:
+            e = gspc::launch_maxpool(static_cast<const float *>(act_bufs[L.src]),
+                                     static_cast<float *>(act_bufs[L.dst]), L.N, L.Cin, L.H, L.W,
+                                     L.KH, L.stride, L.pad, out_dim(L.H, L.KH, L.stride, L.pad),
+                                     out_dim(L.W, L.KW, L.stride, L.pad), t_stream);
+            break;
+        case GSPC_OP_ADD:
+            e = gspc::launch_add(static_cast<const float *>(act_bufs[L.src]),
+                                 static_cast<const float *>(act_bufs[L.src2]),
+                                 static_cast<float *>(act_bufs[L.dst]), elems,
+                                 (L.flags & GSPC_FLAG_RELU) ? 1 : 0, t_stream);
+            break;
+        case GSPC_OP_RELU:
+            e = gspc::launch_relu(static_cast<const float *>(act_bufs[L.src]),
+                                  static_cast<float *>(act_bufs[L.dst]), elems, t_stream);
+            break;
+        }
+        if (e != hipSuccess) rc = hip_fail(e, "chain op launch");
+        if (per_layer_ms) (void)hipEventRecord(ev[i + 1], t_stream);
+    }
+    if (per_layer_ms) {
+        hipError_t e = hipStreamSynchronize(t_stream);
+        if (e != hipSuccess && rc == GSPC_OK) rc = hip_fail(e, "hipStreamSynchronize");
+        for (int i = 0; i < n_layers; ++i) {
+            float ms = 0.f;
+            if (rc == GSPC_OK) (void)hipEventElapsedTime(&ms, ev[i], ev[i + 1]);
+            per_layer_ms[i] = ms;
+        }
+        for (auto &e2 : ev) (void)hipEventDestroy(e2);
+    }
+    return rc;
+}
+
+}  // extern "C"

@@ -1,0 +1,144 @@
+// Stage 1 of GSPC (kernel reshape, Section III-B of arXiv 2006.09791) for the
+// GPU layouts, its inverse, and the fp32 -> bf16 input cast.
+#include "gspc_internal.h"
+
+namespace gspc {
+
+struct PackArgs {
+    int groups, CPG, KPG, KH, KW, Kred, KPGd;
+    int variant, ksub, ksteps, mtiles;
+    int to_bf16;
+};
+
+__device__ __forceinline__ float round_bf16(float v) {
+    uint32_t u = __float_as_uint(v);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return v;  // NaN stays NaN
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return __uint_as_float(u & 0xffff0000u);
+}
+
+// total covers the section plus the alignment gap behind it, which is zeroed.
+__global__ void pack_direct_kernel(const float *__restrict__ w, float *__restrict__ out,
+                                   PackArgs a, size_t section, size_t total) {
+    size_t d = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (d >= total) return;
+    if (d >= section) {
+        out[d] = 0.f;
+        return;
+    }
+    const int o = (int)(d % a.KPGd);
+    const size_t r = d / a.KPGd;
+    const int k = (int)(r % a.Kred);
+    const int j = (int)(r / a.Kred);
+    float v = 0.f;
+    if (o < a.KPG) {
+        v = w[((size_t)j * a.KPG + o) * a.Kred + k];
+        if (a.to_bf16) v = round_bf16(v);
+    }
+    out[d] = v;
+}
+
+__global__ void pack_mfma_kernel(const float *__restrict__ w, float *__restrict__ out,
+                                 PackArgs a, size_t total) {
+    size_t d = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (d >= total) return;
+    const int lane = (int)(d % 64);
+    size_t r = d / 64;
+    const int ks = (int)(r % a.ksteps);
+    r /= a.ksteps;
+    const int mt = (int)(r % a.mtiles);
+    const int j = (int)(r / a.mtiles);
+    const int taps = a.KH * a.KW;
+    const int cblk = ks / taps, tap = ks % taps;
+    const int oc_in = lane % a.variant;
+    const int sub = a.variant == 4 ? 0 : lane / a.variant;
+    const int c = cblk * a.ksub + sub;
+    float v = 0.f;
+    if (c < a.CPG) {
+        const int oc = j * a.KPG + mt * a.variant + oc_in;
+        v = w[(size_t)oc * a.Kred + (size_t)c * taps + tap];
+        if (a.to_bf16) v = round_bf16(v);
+    }
+    out[d] = v;
+}
+
+__global__ void unpack_kernel(const float *__restrict__ sec, float *__restrict__ w, PackArgs a,
+                              int from_mfma, size_t total) {
+    size_t d = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (d >= total) return;
+    const int k = (int)(d % a.Kred);
+    const int oc = (int)(d / a.Kred);
+    const int j = oc / a.KPG, o = oc % a.KPG;
+    if (!from_mfma) {
+        w[d] = sec[((size_t)j * a.Kred + k) * a.KPGd + o];
+        return;
+    }
+    const int taps = a.KH * a.KW;
+    const int c = k / taps, tap = k % taps;
+    const int mt = o / a.variant, oc_in = o % a.variant;
+    const int cblk = c / a.ksub, sub = c % a.ksub;
+    const int lane = (a.variant == 4 ? 0 : sub * a.variant) + oc_in;
+    const int ks = cblk * taps + tap;
+    w[d] = sec[(((size_t)j * a.mtiles + mt) * a.ksteps + ks) * 64 + lane];
+}
+
+__global__ void cast_bf16_kernel(const float *__restrict__ in, uint16_t *__restrict__ out,
+                                 size_t count) {
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const size_t step = (size_t)gridDim.x * blockDim.x;
+    for (; i < count; i += step) out[i] = (uint16_t)(__float_as_uint(round_bf16(in[i])) >> 16);
+}
+
+static PackArgs make_args(const gspc_packed *h) {
+    PackArgs a;
+    a.groups = h->groups; a.CPG = h->geom.CPG; a.KPG = h->geom.KPG; a.KH = h->KH; a.KW = h->KW;
+    a.Kred = h->geom.Kred; a.KPGd = h->geom.KPGd;
+    a.variant = h->geom.variant; a.ksub = h->geom.ksub; a.ksteps = h->geom.ksteps;
+    a.mtiles = h->geom.mtiles;
+    a.to_bf16 = h->dtype == GSPC_BF16;
+    return a;
+}
+
+static unsigned blocks_for(size_t total, int threads) {
+    return (unsigned)((total + threads - 1) / threads);
+}
+
+hipError_t launch_pack_weights(const float *w, const gspc_packed *h, hipStream_t s) {
+    const PackArgs a = make_args(h);
+    float *dsec = static_cast<float *>(h->dev);
+    const size_t nd = h->geom.direct_bytes / sizeof(float);
+    const size_t nd_gap = h->geom.mfma_offset / sizeof(float);
+    hipLaunchKernelGGL(pack_direct_kernel, dim3(blocks_for(nd_gap, 256)), dim3(256), 0, s, w, dsec, a,
+                       nd, nd_gap);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    if (h->geom.variant != kMfmaNone) {
+        float *msec = reinterpret_cast<float *>(static_cast<char *>(h->dev) + h->geom.mfma_offset);
+        const size_t nm = h->geom.mfma_bytes / sizeof(float);
+        hipLaunchKernelGGL(pack_mfma_kernel, dim3(blocks_for(nm, 256)), dim3(256), 0, s, w, msec, a, nm);
+        e = hipGetLastError();
+    }
+    return e;
+}
+
+hipError_t launch_unpack_weights(const gspc_packed *h, int which, float *w, hipStream_t s) {
+    const PackArgs a = make_args(h);
+    const size_t total = (size_t)h->Cout * h->geom.Kred;
+    const int from_mfma = which == GSPC_PATH_MFMA;
+    const float *sec = from_mfma
+                           ? reinterpret_cast<const float *>(static_cast<const char *>(h->dev) +
+                                                             h->geom.mfma_offset)
+                           : static_cast<const float *>(h->dev);
+    hipLaunchKernelGGL(unpack_kernel, dim3(blocks_for(total, 256)), dim3(256), 0, s, sec, w, a,
+                       from_mfma, total);
+    return hipGetLastError();
+}
+
+hipError_t launch_cast_bf16(const float *in, size_t count, uint16_t *out, hipStream_t s) {
+    size_t blocks = (count + 255) / 256;
+    if (blocks > 65536) blocks = 65536;
+    hipLaunchKernelGGL(cast_bf16_kernel, dim3((unsigned)blocks), dim3(256), 0, s, in, out, count);
+    return hipGetLastError();
+}
+
+}  // namespace gspc

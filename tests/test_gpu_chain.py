@@ -1,0 +1,73 @@
+"""GPU parity of whole layer chains (gspc_run_layer_chain) against the oracle."""
+import numpy as np
+import pytest
+
+from helpers import TOL_F32, gpu_chain, oracle_chain, rel_err
+from paper_2006_09791_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+
+def _run(chain, config_id, seed):
+    import torch
+    from paper_2006_09791_amd import binding as b
+    x0 = wl.make_input(chain.input_shape, seed)
+    weights = chain.make_weights(config_id)
+    lc, bufs = gpu_chain(chain, x0, weights)
+    ms = b.gspc_run_layer_chain(lc, per_layer_ms=True)
+    assert len(ms) == len(chain.layers) and all(m >= 0 for m in ms)
+    n_out = int(np.prod(chain.out_shape))
+    got = bufs[chain.out_buf][:n_out].cpu().numpy().reshape(chain.out_shape)
+    # asynchronous form gives the same bits
+    b.gspc_run_layer_chain(lc)
+    torch.cuda.synchronize()
+    again = bufs[chain.out_buf][:n_out].cpu().numpy().reshape(chain.out_shape)
+    assert np.array_equal(got, again)
+    ref = oracle_chain(chain, x0, weights)[chain.out_buf]
+    return got, ref
+
+
+@pytest.mark.parametrize("g", [1, 2, 4, 8, 16])
+def test_wrn_chain_n1(g):
+    chain = wl.wrn_chain(1, g)
+    got, ref = _run(chain, 2, wl.make_seed(2, 999, g))
+    assert np.abs(ref).max() > 0
+    assert rel_err(got, ref) < TOL_F32
+
+
+def test_wrn_chain_n3_g4():
+    chain = wl.wrn_chain(3, 4)
+    got, ref = _run(chain, 2, 77)
+    assert rel_err(got, ref) < TOL_F32
+
+
+@pytest.mark.parametrize("g", [2, 32])
+def test_resnet34_chain_n1(g):
+    chain = wl.resnet34_chain(1, g)
+    got, ref = _run(chain, 3, wl.make_seed(3, 999, g))
+    assert np.abs(ref).max() > 0
+    assert rel_err(got, ref) < TOL_F32
+
+
+@pytest.mark.parametrize("C,hw,stride", [(32, 112, 1), (64, 112, 2), (256, 28, 1), (1024, 7, 2)])
+def test_depthwise_pointwise_chain(C, hw, stride):
+    chain = wl.mobilenet_dw_chain(1, C, hw, stride)
+    got, ref = _run(chain, 4, wl.make_seed(4, C, stride))
+    assert rel_err(got, ref) < TOL_F32
+
+
+def test_chain_validation_precedes_launch():
+    import torch
+    from paper_2006_09791_amd import binding as b
+    chain = wl.mobilenet_dw_chain(1, 8, 10, 1)
+    x0 = wl.make_input(chain.input_shape, 1)
+    weights = chain.make_weights(4)
+    lc, bufs = gpu_chain(chain, x0, weights)
+    bufs[1].fill_(123.0)
+    lc.bytes[2] = 16       # last layer's output buffer too small
+    torch.cuda.synchronize()
+    with pytest.raises(b.GspcError) as e:
+        b.gspc_run_layer_chain(lc)
+    assert e.value.code == -6
+    torch.cuda.synchronize()
+    assert float(bufs[1].min()) == 123.0    # first layer was not launched either

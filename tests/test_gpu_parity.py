@@ -1,0 +1,198 @@
+"""GPU parity: libgspc (through its C ABI) against the CPU oracle, element by
+element on the same seeded inputs."""
+import numpy as np
+import pytest
+
+import oracle
+from helpers import TOL_BF16, TOL_F32, rel_err
+from paper_2006_09791_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    import torch
+    from paper_2006_09791_amd import binding as b
+    assert torch.cuda.is_available()
+    b.load()
+    b.gspc_set_stream()
+    b.gspc_force_path(b.PATH_AUTO)
+    return torch, b
+
+
+def run_conv(gpu, s, seed, path=None, dtype=None, poison=True):
+    """Runs one layer on the GPU; returns (y_gpu float32 ndarray, x, w, kernel name)."""
+    torch, b = gpu
+    dev = torch.device("cuda:0")
+    x = wl.make_input((s.N, s.Cin, s.H, s.W), seed)
+    w = wl.make_weight(s.Cout, s.Cin // s.groups, s.KH, s.KW, seed)
+    dt = dtype if dtype is not None else b.GSPC_F32
+    pw = b.gspc_pack_weights(torch.from_numpy(w).to(dev), s.groups, dt)
+    xd = torch.from_numpy(x).to(dev)
+    if dt == b.GSPC_BF16:
+        xd = b.gspc_pack_input_bf16(xd)
+    ho, wo = b.gspc_output_dims(s.H, s.W, s.KH, s.KW, s.stride, s.pad)
+    y = torch.full((s.N, s.Cout, ho, wo), float("nan"), dtype=torch.float32, device=dev)
+    b.gspc_force_path(path if path is not None else b.PATH_AUTO)
+    try:
+        b.gspc_conv2d_grouped(xd, pw, s.N, s.Cin, s.H, s.W, s.Cout, s.KH, s.KW, s.stride, s.pad,
+                              s.groups, y)
+        name = b.gspc_last_kernel()
+    finally:
+        b.gspc_force_path(b.PATH_AUTO)
+    torch.cuda.synchronize()
+    return y.cpu().numpy(), x, w, name
+
+
+def check(gpu, s, seed, path=None, tol=TOL_F32):
+    y, x, w, name = run_conv(gpu, s, seed, path)
+    ref = oracle.conv2d_grouped(x, w, s.stride, s.pad, s.groups, threads=8)
+    assert not np.isnan(y).any(), f"{name}: output not fully written for {s}"
+    err = rel_err(y, ref)
+    assert err < tol, f"{name}: rel err {err:.3e} for {s}"
+    return name
+
+
+def test_config1(gpu):
+    name = check(gpu, wl.config1(), seed=0)
+    print("config1 ran on", name)
+
+
+S = wl.ConvShape
+SWEEP = [
+    # N Cin H W Cout KH KW stride pad groups
+    S(2, 8, 9, 7, 8, 3, 3, 1, 1, 1),
+    S(1, 6, 5, 4, 4, 3, 3, 2, 1, 2),       # KPG = 2: direct only
+    S(3, 12, 11, 13, 24, 3, 3, 1, 1, 3),   # KPG = 8
+    S(2, 16, 10, 10, 16, 3, 3, 2, 1, 4),   # KPG = 4
+    S(1, 32, 17, 19, 32, 3, 3, 1, 1, 2),   # KPG = 16
+    S(2, 32, 16, 16, 64, 3, 3, 2, 1, 2),   # KPG = 32, CPG = 16
+    S(1, 64, 8, 8, 64, 3, 3, 1, 1, 1),     # KPG = 64
+    S(3, 128, 8, 8, 128, 3, 3, 1, 1, 1),   # KPG = 128, odd batch vs images per block
+    S(1, 3, 32, 32, 32, 3, 3, 1, 1, 1),    # stem: CPG = 3 padded to the MFMA k extent
+    S(1, 3, 40, 40, 64, 7, 7, 2, 3, 1),    # 7x7 stride 2
+    S(2, 32, 32, 32, 64, 1, 1, 2, 0, 1),   # 1x1 stride 2 shortcut
+    S(1, 16, 14, 14, 32, 1, 1, 1, 0, 1),   # pointwise
+    S(1, 8, 12, 12, 8, 3, 3, 1, 1, 8),     # depthwise
+    S(2, 8, 7, 7, 8, 3, 3, 2, 1, 8),       # depthwise stride 2, odd size
+    S(1, 8, 9, 9, 16, 3, 3, 1, 1, 8),      # depthwise, channel multiplier 2
+    S(1, 10, 9, 8, 15, 2, 3, 1, 0, 5),     # KH != KW, no padding
+    S(1, 4, 6, 6, 4, 5, 5, 1, 2, 2),       # 5x5
+    S(1, 8, 5, 5, 8, 3, 3, 3, 2, 2),       # stride 3, pad 2
+    S(1, 64, 56, 56, 64, 3, 3, 1, 1, 2),   # ResNet-like row blocks with ragged tail
+    S(1, 128, 28, 28, 128, 3, 3, 1, 1, 32),
+    S(1, 512, 7, 7, 512, 3, 3, 1, 1, 32),
+]
+
+
+@pytest.mark.parametrize("s", SWEEP, ids=lambda s: "x".join(map(str, s)))
+def test_sweep_auto(gpu, s):
+    check(gpu, s, seed=11)
+
+
+@pytest.mark.parametrize("s", SWEEP, ids=lambda s: "x".join(map(str, s)))
+def test_sweep_direct(gpu, s):
+    _, b = gpu
+    name = check(gpu, s, seed=12, path=b.PATH_DIRECT)
+    assert "direct" in name or "depthwise" in name
+
+
+@pytest.mark.parametrize("s", SWEEP, ids=lambda s: "x".join(map(str, s)))
+def test_sweep_mfma(gpu, s):
+    _, b = gpu
+    try:
+        name = check(gpu, s, seed=13, path=b.PATH_MFMA)
+    except b.GspcError as e:
+        assert e.code == -8      # family has no instance for this layer
+        pytest.skip("no matrix-core instance for this shape")
+    assert "mfma" in name
+
+
+@pytest.mark.parametrize("g", [1, 2, 4, 8, 16])
+def test_wrn_layers_n4(gpu, g):
+    for i, s in enumerate(wl.wrn_grouped_shapes(4, g)):
+        check(gpu, s, seed=wl.make_seed(2, i, g))
+
+
+@pytest.mark.parametrize("g", [2, 8, 32])
+def test_resnet_layers_n1(gpu, g):
+    for i, s in enumerate(wl.resnet34_grouped_shapes(1, g)):
+        check(gpu, s, seed=wl.make_seed(3, i, g))
+
+
+def test_depthwise_pairs(gpu):
+    for i, (dw, pw) in enumerate(wl.depthwise_pairs(1)):
+        check(gpu, dw, seed=wl.make_seed(4, 2 * i, dw.groups))
+        check(gpu, pw, seed=wl.make_seed(4, 2 * i + 1, 1))
+
+
+def test_pack_is_a_permutation(gpu):
+    torch, b = gpu
+    dev = torch.device("cuda:0")
+    for (Cout, Cin, K, g) in [(64, 64, 3, 4), (24, 12, 3, 3), (6, 4, 3, 2), (128, 128, 1, 1),
+                              (32, 3, 7, 1), (16, 16, 3, 16)]:
+        w = wl.make_weight(Cout, Cin // g, K, K, 5)
+        pw = b.gspc_pack_weights(torch.from_numpy(w).to(dev), g)
+        back = b.gspc_unpack_weights(pw, b.PATH_DIRECT).cpu().numpy()
+        assert np.array_equal(back, w)
+        if pw.info()["has_mfma"]:
+            back = b.gspc_unpack_weights(pw, b.PATH_MFMA).cpu().numpy()
+            assert np.array_equal(back, w)
+        # padding lanes are zero and nothing else was invented: the packed
+        # bytes hold every weight at least once and otherwise only zeros
+        n = b.gspc_packed_weight_bytes(Cin, Cout, K, K, g)
+        off = (-pw.storage.data_ptr()) % 256
+        flat = pw.storage[off:off + n].view(torch.float32).cpu().numpy()
+        vals = set(np.unique(flat).tolist())
+        assert vals <= set(np.unique(w).tolist()) | {0.0}
+
+
+def test_bf16_cast_matches_host_rounding(gpu):
+    torch, b = gpu
+    x = wl.make_input((3, 5, 7, 11), 6)
+    x[0, 0, 0, :4] = [0.0, -0.0, 1.0 + 2.0 ** -8, 1.0 + 3 * 2.0 ** -8]   # ties
+    bits, _ = wl.round_to_bf16(x)
+    got = b.gspc_pack_input_bf16(torch.from_numpy(x).cuda()).view(torch.int16).cpu().numpy()
+    assert np.array_equal(got.view(np.uint16), bits)
+
+
+@pytest.mark.parametrize("s", [
+    S(2, 64, 14, 14, 64, 3, 3, 1, 1, 2),
+    S(2, 64, 14, 14, 128, 3, 3, 2, 1, 8),
+    S(1, 64, 12, 12, 64, 3, 3, 1, 1, 32),
+], ids=lambda s: "x".join(map(str, s)))
+def test_bf16_layers(gpu, s):
+    torch, b = gpu
+    for path in (b.PATH_AUTO, b.PATH_DIRECT):
+        y, x, w, name = run_conv(gpu, s, seed=21, path=path, dtype=b.GSPC_BF16)
+        _, xr = wl.round_to_bf16(x)
+        _, wr = wl.round_to_bf16(w)
+        # primary: same rounded operands on both sides, only accumulation differs
+        ref_r = oracle.conv2d_grouped(xr, wr, s.stride, s.pad, s.groups, threads=8)
+        assert rel_err(y, ref_r) < 1e-4, name
+        # secondary: against the un-rounded data, the stated bf16 tolerance
+        ref = oracle.conv2d_grouped(x, w, s.stride, s.pad, s.groups, threads=8)
+        assert rel_err(y, ref) < TOL_BF16, name
+
+
+def test_rerun_is_bit_identical(gpu):
+    s = wl.wrn_grouped_shapes(2, 2)[2]
+    y1, *_ = run_conv(gpu, s, seed=31)
+    y2, *_ = run_conv(gpu, s, seed=31)
+    assert np.array_equal(y1, y2)
+
+
+def test_mismatch_and_errors_on_device(gpu):
+    torch, b = gpu
+    dev = torch.device("cuda:0")
+    w = wl.make_weight(8, 4, 3, 3, 1)
+    pw = b.gspc_pack_weights(torch.from_numpy(w).to(dev), 2)
+    x = torch.zeros((1, 8, 6, 6), device=dev)
+    y = torch.zeros((1, 8, 6, 6), device=dev)
+    with pytest.raises(b.GspcError) as e:
+        b.gspc_conv2d_grouped(x, pw, 1, 8, 6, 6, 8, 3, 3, 1, 1, 4, y)
+    assert e.value.code == -5
+    with pytest.raises(b.GspcError) as e:
+        b.gspc_conv2d_grouped(x, pw, 1, 8, 1, 1, 8, 3, 3, 1, 0, 2, y)
+    assert e.value.code == -2
