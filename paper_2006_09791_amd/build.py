@@ -11,12 +11,14 @@ OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libgspc.so")
 
 SOURCES = ["gspc_api.cpp", "pack_kernels.hip", "chain_kernels.hip",
-           "direct_kernels.hip", "mfma_kernels.hip"]
+           "direct_kernels.hip", "mfma_kernels.hip", "mfma4_kernels.hip"]
 
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-x", "hip",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wall", "-Wno-unused-command-line-argument",
          "-I", os.path.join(ROOT, "include"), "-I", CSRC]
+if os.environ.get("GSPC_PHASE_TIMING"):      # developer aid: per-phase timestamps
+    FLAGS.append("-DGSPC_PHASE_TIMING")
 
 
 def _hipcc():

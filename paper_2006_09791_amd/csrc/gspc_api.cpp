@@ -76,7 +76,7 @@ int prepare_conv(const void *input, const gspc_packed_t *pw, int N, int Cin, int
         return fail(GSPC_ERR_DIM, "tensor with 2^31 or more elements is not supported");
     p->x = input;
     p->wd = reinterpret_cast<const float *>(pw->dev);
-    p->wm = pw->geom.variant != gspc::kMfmaNone
+    p->wm = pw->geom.mfma_bytes
                 ? reinterpret_cast<const float *>(static_cast<const char *>(pw->dev) +
                                                   pw->geom.mfma_offset)
                 : nullptr;
@@ -118,11 +118,10 @@ PackGeom make_pack_geom(int Cin, int Cout, int KH, int KW, int groups, int /*dty
     g.Kred = g.CPG * KH * KW;
     g.KPGd = round_up(g.KPG, 4);
     g.direct_bytes = (size_t)groups * g.Kred * g.KPGd * sizeof(float);
-    if (g.KPG % 32 == 0) g.variant = kMfma32;
-    else if (g.KPG % 16 == 0) g.variant = kMfma16;
+    if (g.KPG % 16 == 0) g.variant = kMfma16;
     else if (g.KPG % 4 == 0) g.variant = kMfma4;
     else g.variant = kMfmaNone;
-    if (g.variant != kMfmaNone) {
+    if (g.variant == kMfma16) {
         g.ksub = mfma_ksub(g.variant);
         g.CPGp = round_up(g.CPG, g.ksub);
         g.ksteps = g.CPGp / g.ksub * KH * KW;
@@ -212,7 +211,7 @@ int gspc_unpack_weights(const gspc_packed_t *packed, int which, void *weight_dev
     if (!valid_handle(packed)) return fail(GSPC_ERR_MISMATCH, "not a packed-weight handle");
     if (which != GSPC_PATH_DIRECT && which != GSPC_PATH_MFMA)
         return fail(GSPC_ERR_ARG, "which must be GSPC_PATH_DIRECT or GSPC_PATH_MFMA");
-    if (which == GSPC_PATH_MFMA && packed->geom.variant == gspc::kMfmaNone)
+    if (which == GSPC_PATH_MFMA && packed->geom.mfma_bytes == 0)
         return fail(GSPC_ERR_ARG, "handle holds no matrix-core section");
     hipError_t e = gspc::launch_unpack_weights(packed, which, static_cast<float *>(weight_dev), t_stream);
     if (e != hipSuccess) return hip_fail(e, "weight unpack launch");
@@ -235,7 +234,7 @@ int gspc_packed_info(const gspc_packed_t *packed, int *Cin, int *Cout, int *KH, 
     if (KW) *KW = packed->KW;
     if (groups) *groups = packed->groups;
     if (dtype) *dtype = packed->dtype;
-    if (has_mfma) *has_mfma = packed->geom.variant != gspc::kMfmaNone;
+    if (has_mfma) *has_mfma = packed->geom.mfma_bytes != 0;
     return GSPC_OK;
 }
 

@@ -14,23 +14,24 @@ constexpr int kVersion = 1;
 
 // Matrix-core tile variants of the implicit-GEMM kernels.  The value is the
 // number of output channels one MFMA instruction covers.
-enum MfmaVariant { kMfmaNone = 0, kMfma4 = 4, kMfma16 = 16, kMfma32 = 32 };
+enum MfmaVariant { kMfmaNone = 0, kMfma4 = 4, kMfma16 = 16 };
 
-// Reduction slots one MFMA instruction consumes per variant (its K extent).
-__host__ __device__ constexpr int mfma_ksub(int variant) {
-    return variant == 32 ? 2 : variant == 16 ? 4 : 1;
-}
+// Reduction slots one MFMA instruction consumes per variant (its K extent):
+// v_mfma_f32_16x16x4_f32 contracts 4, v_mfma_f32_4x4x1_16b_f32 contracts 1.
+__host__ __device__ constexpr int mfma_ksub(int variant) { return variant == 16 ? 4 : 1; }
 
 inline int round_up(int v, int m) { return (v + m - 1) / m * m; }
 
 // Geometry of the two sections of a packed-weight buffer.
 //   direct section : fp32 [g][Kred][KPGd], Kred = CPG*KH*KW ordered (c, kh, kw),
 //                    KPGd = KPG rounded up to a multiple of 4, zero padded.
-//   mfma section   : fp32 [g][KPG/variant][ksteps][64], the A operand of one
-//                    MFMA per (k-step, lane); k-steps ordered (c / ksub, kh, kw)
-//                    with CPG zero-padded to a multiple of ksub; lane l holds
-//                    filter (l % variant) [all variants] and reduction slot
-//                    c = cblk*ksub + l / variant [variants 32, 16].
+//   mfma section   : (variant 16 only) fp32 [g][ksteps][KPG/16][64], the A operand
+//                    of one v_mfma_f32_16x16x4_f32 per (k-step, filter tile,
+//                    lane); k-steps ordered (c / 4, kh, kw) with CPG zero-padded
+//                    to a multiple of 4; lane l holds filter l % 16 of its tile
+//                    at reduction slot c = cblk*4 + l / 16.
+//   Variant 4 (KPG a multiple of 4 but not of 16) runs the 4x4x1 MFMA kernel,
+//   which reads its operands from the direct section.
 struct PackGeom {
     int CPG, KPG, Kred, KPGd;
     int variant;   // MfmaVariant
@@ -73,6 +74,14 @@ hipError_t launch_direct(const ConvParams &p, hipStream_t s, const char **name);
 hipError_t launch_mfma(const ConvParams &p, const PackGeom &g, hipStream_t s,
                        const char **name);
 bool mfma_supported(const ConvParams &p, const PackGeom &g);
+
+// 4x4x1 MFMA kernel (weights held in registers); plan is opaque to the caller.
+struct Mfma4Plan {
+    int inst;        // index of the kernel instance
+    int data[40];    // tile geometry, see mfma4_kernels.hip
+};
+bool plan_mfma4(const ConvParams &p, const PackGeom &g, Mfma4Plan *out);
+hipError_t launch_mfma4(const ConvParams &p, const Mfma4Plan &plan, hipStream_t s, const char **name);
 
 hipError_t launch_pack_weights(const float *w, const gspc_packed *h, hipStream_t s);
 hipError_t launch_unpack_weights(const gspc_packed *h, int which, float *w, hipStream_t s);

@@ -7,313 +7,502 @@
 // zero-haloed input tile is staged in LDS (the paper's input reshape, fused)
 // and every lane reads its own (pixel, k) element from it.  Results go
 // straight to NCHW (the paper's output reshape, fused away).
-#include "gspc_internal.h"
+#include <cstdlib>
+#include <cstring>
+#include <unordered_map>
+
+#include "conv_common.h"
 
 namespace gspc {
 
-typedef float f32x4 __attribute__((ext_vector_type(4)));
-typedef float f32x16 __attribute__((ext_vector_type(16)));
+// ---------------------------------------------------------------------------
+// 16x16x4 kernel: KPG a multiple of 16.
+//
+// v_mfma_f32_16x16x4_f32 operand layout (lane l of 64):
+//   A: filter row l%16, reduction slot l/16      B: slot l/16, pixel column l%16
+//   D: register r holds (row 4*(l/16) + r, column l%16)
+// One k-step contracts 4 input channels at one kernel tap (kh, kw).
+//
+// Block = WM x WP waves; a wave owns MI x NI tiles = 16*MI filters x 16*NI
+// pixels.  The block's pixels are NB images x TH output rows x Wout columns,
+// flattened in that order and cut into runs of 16.  The reduction runs over
+// chunks of CK channels; chunk i+1 is fetched from global memory into
+// registers while chunk i is multiplied out of LDS (two LDS buffers).
+// ---------------------------------------------------------------------------
+constexpr int kTmax16 = 4, kWmax16 = 4;
 
-template <int VAR> struct Mma;
-
-// v_mfma_f32_32x32x2_f32: A lane l = (row l%32, k l/32), B lane l = (k l/32, col l%32),
-// D reg r of lane l = (row 8*(r/4) + 4*(l/32) + r%4, col l%32).
-template <> struct Mma<32> {
-    static constexpr int KSUB = 2, PT = 32, NACC = 16;
-    typedef f32x16 acc_t;
-    __device__ static __forceinline__ acc_t run(float a, float b, acc_t c) {
-        return __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, c, 0, 0, 0);
-    }
-    __device__ static __forceinline__ int row(int r, int lane) { return 8 * (r / 4) + 4 * (lane / 32) + r % 4; }
-    __device__ static __forceinline__ int ksub(int lane) { return lane / 32; }
-};
-
-// v_mfma_f32_16x16x4_f32: A lane l = (row l%16, k l/16), B lane l = (k l/16, col l%16),
-// D reg r of lane l = (row 4*(l/16) + r, col l%16).
-template <> struct Mma<16> {
-    static constexpr int KSUB = 4, PT = 16, NACC = 4;
-    typedef f32x4 acc_t;
-    __device__ static __forceinline__ acc_t run(float a, float b, acc_t c) {
-        return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0);
-    }
-    __device__ static __forceinline__ int row(int r, int lane) { return 4 * (lane / 16) + r; }
-    __device__ static __forceinline__ int ksub(int lane) { return lane / 16; }
-};
-
-// v_mfma_f32_4x4x1_16b_f32: sixteen independent 4x4 outer products.  Block
-// l/4 of lane l; A lane = row l%4, B lane = col l%4, D reg r = (row r, col l%4).
-// The packed A operand repeats the same four filters in every block, so the
-// sixteen blocks act as 64 pixel columns.
-template <> struct Mma<4> {
-    static constexpr int KSUB = 1, PT = 64, NACC = 4;
-    typedef f32x4 acc_t;
-    __device__ static __forceinline__ acc_t run(float a, float b, acc_t c) {
-        return __builtin_amdgcn_mfma_f32_4x4x1f32(a, b, c, 0, 0, 0);
-    }
-    __device__ static __forceinline__ int row(int r, int /*lane*/) { return r; }
-    __device__ static __forceinline__ int ksub(int /*lane*/) { return 0; }
-};
-
-// Block tiling chosen on the host.
-struct MfmaTile {
-    int NB, TH;            // images and output rows per block
-    int IHt, LW, IMG, PLANE;  // staged rows, LDS row pitch, floats per image, per channel
-    int CK;                // input channels staged per chunk (multiple of KSUB, divides CPGp)
-    int CPGp;
+struct Tile16 {
+    int NB, TH, IHt;         // images, output rows per block; staged input rows
+    int LW, IMG, PLANE, XO;  // LDS row pitch, floats per image / per channel, column of input col 0
+    int CK, nchunks;         // channels per chunk (multiple of 4), number of chunks
     int row_blocks, img_blocks, oc_blocks;
-    int in_floats;         // CK * PLANE
-    int ksteps, mtiles;    // of the packed section
+    int tpr_log2, vec;       // threads per staged row (log2); 1 = 4-wide loads
+    int tasks;               // staged rows per chunk = CK*NB*IHt
+    int xslots, wslots;      // staged rows / weight float4 per thread per chunk
+    int ksteps, mtiles;      // geometry of the packed weight section
+    int in_floats, w_floats; // per LDS buffer (a buffer is in | w | 4 spare floats)
+    unsigned m_IHt, m_NB, m_ppi, m_Wout, m_rowb, m_ocb;  // multiply-high reciprocals (0 = divisor 1)
+    unsigned x_bytes, w_bytes, y_bytes;                  // extents for the buffer descriptors
 };
 
-__device__ __forceinline__ float ld_in(const float *p, size_t i) { return p[i]; }
-__device__ __forceinline__ float ld_in(const uint16_t *p, size_t i) {
-    return __uint_as_float((uint32_t)p[i] << 16);
-}
+#ifdef GSPC_PHASE_TIMING
+__device__ unsigned long long g_phase[8 * 4096];
+#define GSPC_STAMP(i)                                                                      \
+    if (threadIdx.x == 0) {                                                                \
+        const unsigned bid = blockIdx.x + blockIdx.y * gridDim.x;                          \
+        if (bid < 4096) g_phase[bid * 8 + (i)] = __builtin_amdgcn_s_memrealtime();         \
+    }
+#else
+#define GSPC_STAMP(i)
+#endif
 
-// Block = WM x WP waves; each wave owns MI x NI MFMA tiles, i.e. VAR*MI filters
-// by PT*NI pixels.  Pixels of a block = NB images x TH output rows x Wout.
-template <int VAR, int MI, int NI, int WM, int WP, int KH, int KW, int S, typename TIN>
-__global__ __launch_bounds__(64 * WM * WP) void conv_mfma(ConvParams p, MfmaTile t) {
-    typedef Mma<VAR> M;
-    constexpr int KSUB = M::KSUB, PT = M::PT, NACC = M::NACC;
-    constexpr int NT = 64 * WM * WP;
-    constexpr int TAPS = KH * KW;
-    extern __shared__ float smem[];
-    float *xs = smem;                 // [CK][PLANE]
-    float *ws = smem + t.in_floats;   // [MI*WM][CK/KSUB*TAPS][64]
+template <int MI, int NI, int WM, int WP, int KH, int KW, int S, typename TIN>
+__global__ __launch_bounds__(64 * WM * WP) void conv_mfma16(ConvParams p, Tile16 t) {
+    GSPC_STAMP(0)
+    constexpr int NT = 64 * WM * WP, TAPS = KH * KW, MIWM = MI * WM;
+    constexpr int TMAX = kTmax16, WMAX = kWmax16, ES = (int)sizeof(TIN);
+    extern __shared__ f32x4 smem4[];
+    float *smem = reinterpret_cast<float *>(smem4);
+    const int buf_floats = t.in_floats + t.w_floats + 4;
+    const unsigned spare = (t.in_floats + t.w_floats) * 4;   // byte offset of a buffer's spare slot
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave / WP, wp = wave % WP;
-    const int rb = blockIdx.x % t.row_blocks, ib = blockIdx.x / t.row_blocks;
-    const int ob = blockIdx.y % t.oc_blocks, j = blockIdx.y / t.oc_blocks;
+    const unsigned ib = fast_div(blockIdx.x, t.m_rowb);
+    const int rb = blockIdx.x - ib * t.row_blocks;
+    const unsigned j = fast_div(blockIdx.y, t.m_ocb);
+    const int ob = blockIdx.y - j * t.oc_blocks;
     const int n0 = ib * t.NB, oh0 = rb * t.TH, ih0 = oh0 * S - p.pad;
     const int ppi = t.TH * p.Wout, tot = t.NB * ppi;
+    const unsigned HW = p.H * p.W;
 
+    const __amdgpu_buffer_rsrc_t rx = make_rsrc(p.x, t.x_bytes);
+    const __amdgpu_buffer_rsrc_t rw = make_rsrc(p.wm, t.w_bytes);
+
+    // ---- weights of a chunk: MIWM*kchunk*64 floats, NT float4 per slot --------
+    const int kchunk = t.CK / 4 * TAPS;
+    const unsigned wrow = t.mtiles * 64 * 4;   // bytes per k-step of the packed section
+    const unsigned wblk = ((j * t.ksteps * t.mtiles + ob * MIWM) * 64) * 4;
+    const unsigned wvoff = (tid / (MIWM * 16)) * wrow + (tid % (MIWM * 16)) * 16;
+    constexpr unsigned kWslot = (NT / (MIWM * 16));   // k-steps advanced per slot
+    static_assert(NT % (MIWM * 16) == 0, "a slot must cover whole k-steps");
+    f32x4 pin[TMAX], pw[WMAX];
+    auto fetch_w = [&](int chunk) __attribute__((always_inline)) {
+        const unsigned so = wblk + chunk * kchunk * wrow;
+#pragma unroll
+        for (int k = 0; k < WMAX; ++k)
+            if (k < t.wslots)
+                pw[k] = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(rw, wvoff, so + k * kWslot * wrow, 0));
+    };
+    fetch_w(0);
+
+    // ---- per-thread input staging plan (identical for every chunk) ---------
+    const int rpp = NT >> t.tpr_log2;
+    const int row0 = tid >> t.tpr_log2, colv = tid & ((1 << t.tpr_log2) - 1);
+    const int vw = t.vec ? 4 : 1;
+    unsigned xoff[TMAX], xlds[TMAX];
+#pragma unroll
+    for (int k = 0; k < TMAX; ++k) {
+        const int task = row0 + k * rpp;
+        xoff[k] = kOob;
+        xlds[k] = spare;
+        if (k < t.xslots && task < t.tasks && colv * vw < p.W) {
+            const int cimg = fast_div(task, t.m_IHt), r = task - cimg * t.IHt;
+            const int c = fast_div(cimg, t.m_NB), img = cimg - c * t.NB;
+            const int ih = ih0 + r, n = n0 + img;
+            xlds[k] = (c * t.PLANE + img * t.IMG + r * t.LW + t.XO + colv * vw) * 4;
+            if (n < p.N && ih >= 0 && ih < p.H && c < p.CPG)
+                xoff[k] = (((n * p.Cin + j * p.CPG + c) * p.H + ih) * p.W + colv * vw) * ES;
+        }
+    }
+    auto fetch_x = [&](int chunk) __attribute__((always_inline)) {
+        const unsigned so = chunk * t.CK * HW * ES;
+#pragma unroll
+        for (int k = 0; k < TMAX; ++k)
+            if (k < t.xslots) pin[k] = buf_load_in<TIN>(rx, xoff[k], so, t.vec);
+    };
+    auto commit = [&](int buf) __attribute__((always_inline)) {
+        char *bb = reinterpret_cast<char *>(smem) + buf * (buf_floats * 4);
+#pragma unroll
+        for (int k = 0; k < TMAX; ++k) {
+            if (k < t.xslots) {
+                if (t.vec) *reinterpret_cast<f32x4 *>(bb + xlds[k]) = pin[k];
+                else *reinterpret_cast<float *>(bb + xlds[k]) = pin[k].x;
+            }
+        }
+        char *wb = bb + t.in_floats * 4 + tid * 16;
+#pragma unroll
+        for (int k = 0; k < WMAX; ++k)
+            if (k < t.wslots) *reinterpret_cast<f32x4 *>(wb + k * NT * 16) = pw[k];
+    };
+    GSPC_STAMP(1)
+    fetch_x(0);
+    GSPC_STAMP(2)
+
+    // ---- per-lane pixel coordinates ----------------------------------------
     int base[NI];
+    unsigned ooff[NI];   // byte offset of this lane's first output element, or kOob
+    const unsigned HWo = p.Hout * p.Wout;
 #pragma unroll
     for (int ni = 0; ni < NI; ++ni) {
-        int q = (wp * NI + ni) * PT + lane % PT;
-        if (q >= tot) q = 0;
-        const int img = q / ppi, rem = q % ppi;
-        const int r = rem / p.Wout, col = rem % p.Wout;
-        base[ni] = M::ksub(lane) * t.PLANE + img * t.IMG + r * S * t.LW + col * S;
+        const int q = (wp * NI + ni) * 16 + (lane & 15);
+        const int qq = q < tot ? q : 0;
+        const int img = fast_div(qq, t.m_ppi), rem = qq - img * ppi;
+        const int r = fast_div(rem, t.m_Wout), col = rem - r * p.Wout;
+        base[ni] = (lane >> 4) * t.PLANE + img * t.IMG + r * S * t.LW + (t.XO - p.pad) + col * S;
+        const int n = n0 + img, oh = oh0 + r;
+        ooff[ni] = (q < tot && n < p.N && oh < p.Hout)
+                       ? (((unsigned)n * p.Cout + j * p.KPG + 4 * (lane >> 4)) * HWo + oh * p.Wout + col) * 4
+                       : kOob;
     }
 
-    typename M::acc_t acc[MI][NI];
+    f32x4 acc[MI][NI];
 #pragma unroll
     for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
-        for (int ni = 0; ni < NI; ++ni)
-#pragma unroll
-            for (int r = 0; r < NACC; ++r) acc[mi][ni][r] = 0.f;
+        for (int ni = 0; ni < NI; ++ni) acc[mi][ni] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    // Halo columns are never written by the staging loop below: clear once.
-    for (int i = tid; i < t.in_floats; i += NT) xs[i] = 0.f;
-
-    const int kchunk = t.CK / KSUB * TAPS;  // k-steps per chunk
-    const TIN *xin = static_cast<const TIN *>(p.x);
-    const int stage_elems = t.CK * t.NB * t.IHt * p.W;
-
-    for (int c0 = 0; c0 < t.CPGp; c0 += t.CK) {
-        __syncthreads();
-        for (int e = tid; e < stage_elems; e += NT) {
-            const int col = e % p.W;
-            int q = e / p.W;
-            const int r = q % t.IHt;
-            q /= t.IHt;
-            const int img = q % t.NB, c = q / t.NB;
-            const int ih = ih0 + r, n = n0 + img, cc = c0 + c;
-            float v = 0.f;
-            if (cc < p.CPG && n < p.N && ih >= 0 && ih < p.H)
-                v = ld_in(xin, (((size_t)n * p.Cin + (size_t)j * p.CPG + cc) * p.H + ih) * p.W + col);
-            xs[c * t.PLANE + img * t.IMG + r * t.LW + col + p.pad] = v;
+    // The staging never writes the halo columns left and right of a row: clear
+    // them once, in both buffers (rows = channels x images x staged rows).
+    {
+        const int rows = 2 * t.CK * t.NB * t.IHt;
+        const int right = t.XO + p.W;
+        for (int i = tid; i < rows; i += NT) {
+            const int b = i >= rows / 2, rr = i - b * (rows / 2);
+            const int cimg = fast_div(rr, t.m_IHt), r = rr - cimg * t.IHt;
+            const int c = fast_div(cimg, t.m_NB), img = cimg - c * t.NB;
+            float *row = smem + b * buf_floats + c * t.PLANE + img * t.IMG + r * t.LW;
+            for (int x = 0; x < t.XO; ++x) row[x] = 0.f;
+            for (int x = right; x < t.LW; ++x) row[x] = 0.f;
         }
-        {
-            const int per_tile = kchunk * 64;
-            const int cb = c0 / KSUB * TAPS;
-            for (int e = tid; e < MI * WM * per_tile; e += NT) {
-                const int mt = e / per_tile, off = e % per_tile;
-                const size_t src =
-                    (((size_t)j * t.mtiles + (size_t)ob * (MI * WM) + mt) * t.ksteps + cb) * 64 + off;
-                ws[e] = p.wm[src];
-            }
-        }
-        __syncthreads();
+    }
+    GSPC_STAMP(3)
+    commit(0);
+    __syncthreads();
+    GSPC_STAMP(4)
 
-        for (int cb = 0; cb < t.CK / KSUB; ++cb) {
-            const float *xrow = xs + cb * KSUB * t.PLANE;
-            const float *wrow = ws + cb * TAPS * 64 + lane;
+    // Software pipeline: iteration ch multiplies chunk ch out of LDS buffer
+    // ch&1 while chunk ch+1 travels global -> registers -> the other buffer.
+    for (int ch = 0; ch < t.nchunks; ++ch) {
+        const bool more = ch + 1 < t.nchunks;
+        if (more) {
+            fetch_w(ch + 1);
+            fetch_x(ch + 1);
+        }
+        const float *xs = smem + (ch & 1) * buf_floats;
+        const float *ws = xs + t.in_floats + (wm * MI) * 64 + lane;
+        for (int cb = 0; cb < t.CK / 4; ++cb) {
+            const float *xrow = xs + cb * 4 * t.PLANE;
+            const float *wrw = ws + cb * TAPS * MIWM * 64;
 #pragma unroll
             for (int kh = 0; kh < KH; ++kh) {
 #pragma unroll
                 for (int kw = 0; kw < KW; ++kw) {
                     float a[MI], b[NI];
 #pragma unroll
-                    for (int mi = 0; mi < MI; ++mi)
-                        a[mi] = wrow[((wm * MI + mi) * kchunk + kh * KW + kw) * 64];
+                    for (int mi = 0; mi < MI; ++mi) a[mi] = wrw[((kh * KW + kw) * MIWM + mi) * 64];
 #pragma unroll
                     for (int ni = 0; ni < NI; ++ni) b[ni] = xrow[base[ni] + kh * t.LW + kw];
 #pragma unroll
                     for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
-                        for (int ni = 0; ni < NI; ++ni) acc[mi][ni] = M::run(a[mi], b[ni], acc[mi][ni]);
+                        for (int ni = 0; ni < NI; ++ni)
+                            acc[mi][ni] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[mi], b[ni], acc[mi][ni], 0, 0, 0);
                 }
             }
         }
-    }
-
-    // Epilogue: optional residual and ReLU, NCHW store.
-    const size_t HWo = (size_t)p.Hout * p.Wout;
-#pragma unroll
-    for (int ni = 0; ni < NI; ++ni) {
-        const int q = (wp * NI + ni) * PT + lane % PT;
-        const int img = q / ppi, rem = q % ppi;
-        const int oh = oh0 + rem / p.Wout, ow = rem % p.Wout, n = n0 + img;
-        if (q >= tot || n >= p.N || oh >= p.Hout) continue;
-#pragma unroll
-        for (int mi = 0; mi < MI; ++mi) {
-#pragma unroll
-            for (int r = 0; r < NACC; ++r) {
-                const int oc = j * p.KPG + (ob * (MI * WM) + wm * MI + mi) * VAR + M::row(r, lane);
-                const size_t idx = ((size_t)n * p.Cout + oc) * HWo + (size_t)oh * p.Wout + ow;
-                float v = acc[mi][ni][r];
-                if (p.res) v += p.res[idx];
-                if (p.relu) v = fmaxf(v, 0.f);
-                p.y[idx] = v;
-            }
+        if (more) {
+            commit((ch + 1) & 1);
+            __syncthreads();
         }
     }
+
+    GSPC_STAMP(5)
+    // ---- epilogue: optional residual and ReLU, NCHW store -------------------
+    // Register r of tile (mi, ni) is filter 16*(tile row) + 4*(lane/16) + r at
+    // this lane's pixel; the 4*(lane/16) part already sits in ooff.
+    const __amdgpu_buffer_rsrc_t ry = make_rsrc(p.y, t.y_bytes);
+    const unsigned oc0 = (ob * MIWM + wm * MI) * 16;
+    if (p.res) {
+        const __amdgpu_buffer_rsrc_t rr = make_rsrc(p.res, t.y_bytes);
+#pragma unroll
+        for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+            for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+                for (int r = 0; r < 4; ++r)
+                    acc[mi][ni][r] += __uint_as_float(
+                        __builtin_amdgcn_raw_buffer_load_b32(rr, ooff[ni], (oc0 + mi * 16 + r) * HWo * 4, 0));
+    }
+#pragma unroll
+    for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+        for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                float v = acc[mi][ni][r];
+                if (p.relu) v = fmaxf(v, 0.f);
+                __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(v), ry, ooff[ni],
+                                                      (oc0 + mi * 16 + r) * HWo * 4, 0);
+            }
+    GSPC_STAMP(6)
 }
+
+#ifdef GSPC_PHASE_TIMING
+extern "C" int gspc_debug_phases(unsigned long long *out, int n) {
+    return (int)hipMemcpyFromSymbol(out, HIP_SYMBOL(g_phase), sizeof(unsigned long long) * n);
+}
+#endif
 
 // ---------------------------------------------------------------------------
 // Host side: tile planning and instance selection.
 // ---------------------------------------------------------------------------
 namespace {
 
-constexpr int kLdsBudget = 40 * 1024;
+constexpr int kLdsBudget16 = 40 * 1024;   // four blocks per CU out of 160 KB
+constexpr size_t kLdsMax = 160 * 1024;
 
-struct Cfg {
-    int VAR, MI, NI, WM, WP;
+struct Cfg16 {
+    int MI, NI, WM, WP;
+    const char *name;
 };
 
-// Instantiated block shapes, per variant, widest filter tile first.
-const Cfg kCfgs[] = {
-    {32, 2, 2, 2, 2},  // 128 filters x 128 pixels
-    {32, 2, 2, 1, 4},  //  64 filters x 256 pixels
-    {32, 1, 2, 1, 4},  //  32 filters x 256 pixels
-    {16, 1, 4, 1, 4},  //  16 filters x 256 pixels
-    {4, 2, 1, 1, 4},   //   8 filters x 256 pixels
-    {4, 1, 1, 1, 4},   //   4 filters x 256 pixels
+// Instantiated block shapes (filters x pixels), largest first.
+const Cfg16 kCfg16[] = {
+    {4, 4, 1, 4, "conv_mfma16<64x256>"},  {2, 4, 1, 4, "conv_mfma16<32x256>"},
+    {4, 2, 1, 4, "conv_mfma16<64x128>"},  {2, 2, 1, 4, "conv_mfma16<32x128>"},
+    {1, 4, 1, 4, "conv_mfma16<16x256>"},  {2, 2, 2, 2, "conv_mfma16<64x64>"},
+    {1, 2, 1, 4, "conv_mfma16<16x128>"},  {2, 1, 1, 4, "conv_mfma16<32x64>"},
+    {1, 1, 1, 4, "conv_mfma16<16x64>"},
 };
+constexpr int kNumCfg16 = sizeof(kCfg16) / sizeof(kCfg16[0]);
 
 bool shape_instantiated(int KH, int KW, int S) {
     return (KH == 3 && KW == 3 && (S == 1 || S == 2)) || (KH == 1 && KW == 1 && (S == 1 || S == 2)) ||
            (KH == 7 && KW == 7 && S == 2);
 }
 
-bool plan(const ConvParams &p, const PackGeom &g, Cfg *cfg_out, MfmaTile *t_out) {
-    if (g.variant == kMfmaNone || !p.wm) return false;
-    if (!shape_instantiated(p.KH, p.KW, p.stride)) return false;
-    for (const Cfg &c : kCfgs) {
-        if (c.VAR != g.variant) continue;
-        const int MB = c.VAR * c.MI * c.WM;
-        if (g.KPG % MB) continue;
-        const int PT = c.VAR == 4 ? 64 : c.VAR;
-        const int PB = PT * c.NI * c.WP;
-        if (p.Wout > PB) continue;
-        MfmaTile t{};
-        const int HWo = p.Hout * p.Wout;
-        if (HWo <= PB) {
-            t.TH = p.Hout;
-            t.NB = PB / HWo;
-            if (t.NB > p.N) t.NB = p.N;
-        } else {
-            t.NB = 1;
-            const int thmax = PB / p.Wout;
-            const int rbk = (p.Hout + thmax - 1) / thmax;
-            t.TH = (p.Hout + rbk - 1) / rbk;
+// LDS bank conflicts (32 banks of 4 bytes) of the first B-operand read of wave
+// 0 for a candidate channel pitch; returns the worst multiplicity of a bank.
+int bank_cost(const ConvParams &p, const Tile16 &t, int plane) {
+    int worst = 0;
+    for (int half = 0; half < 2; ++half) {
+        int cnt[32] = {0};
+        for (int l = 32 * half; l < 32 * half + 32; ++l) {
+            int q = l & 15;
+            const int ppi = t.TH * p.Wout;
+            if (q >= t.NB * ppi) q = 0;
+            const int img = q / ppi, rem = q % ppi, r = rem / p.Wout, col = rem % p.Wout;
+            const int a = (l >> 4) * plane + img * t.IMG + r * p.stride * t.LW + col * p.stride;
+            ++cnt[a & 31];
         }
-        t.IHt = (t.TH - 1) * p.stride + p.KH;
-        t.LW = p.W + 2 * p.pad;
-        t.IMG = t.IHt * t.LW;
-        t.PLANE = t.NB * t.IMG;
-        t.CPGp = g.CPGp;
-        t.ksteps = g.ksteps;
-        t.mtiles = g.mtiles;
-        t.row_blocks = (p.Hout + t.TH - 1) / t.TH;
-        t.img_blocks = (p.N + t.NB - 1) / t.NB;
-        t.oc_blocks = g.KPG / MB;
-        // Largest chunk (in k-blocks of ksub channels) that divides CPGp/ksub and fits the budget.
-        const int cblks = g.CPGp / g.ksub;
-        int best = 0;
-        for (int d = 1; d <= cblks; ++d) {
-            if (cblks % d) continue;
-            const size_t bytes = ((size_t)d * g.ksub * t.PLANE +
-                                  (size_t)c.MI * c.WM * d * p.KH * p.KW * 64) * sizeof(float);
-            if (bytes <= (size_t)kLdsBudget) best = d;
-        }
-        if (!best) continue;
-        t.CK = best * g.ksub;
-        t.in_floats = t.CK * t.PLANE;
-        if ((long)t.row_blocks * t.img_blocks > 2147483647L || p.groups * t.oc_blocks > 65535) continue;
-        *cfg_out = c;
-        *t_out = t;
-        return true;
+        for (int b = 0; b < 32; ++b) worst = cnt[b] > worst ? cnt[b] : worst;
     }
-    return false;
+    return worst;
 }
 
-template <int VAR, int MI, int NI, int WM, int WP, int KH, int KW, int S, typename TIN>
-hipError_t launch_inst(const ConvParams &p, const MfmaTile &t, hipStream_t s) {
-    const size_t lds = ((size_t)t.in_floats + (size_t)MI * WM * (t.CK / Mma<VAR>::KSUB) * KH * KW * 64) *
-                       sizeof(float);
+bool plan16_cfg(const ConvParams &p, const PackGeom &g, const Cfg16 &c, Tile16 *out) {
+    const int MB = 16 * c.MI * c.WM, PB = 16 * c.NI * c.WP, NT = 64 * c.WM * c.WP;
+    if (g.KPG % MB) return false;
+    Tile16 t{};
+    if (!split_pixels(p, PB, &t.NB, &t.TH)) return false;
+    t.IHt = (t.TH - 1) * p.stride + p.KH;
+    t.vec = p.W % 4 == 0;
+    if (t.vec) {
+        t.XO = 4 * ((p.pad + 3) / 4);
+        t.LW = round_up(t.XO + p.W + p.pad, 4);
+    } else {
+        t.XO = p.pad;
+        t.LW = p.W + 2 * p.pad;
+    }
+    t.IMG = t.IHt * t.LW;
+    const int plane0 = round_up(t.NB * t.IMG, 4);
+    int best_pad = 0, best_cost = 1 << 30;
+    for (int pad = 0; pad < 32; pad += 4) {
+        const int cost = bank_cost(p, t, plane0 + pad);
+        if (cost < best_cost) {
+            best_cost = cost;
+            best_pad = pad;
+        }
+    }
+    t.PLANE = plane0 + best_pad;
+    const int cols = t.vec ? p.W / 4 : p.W;
+    t.tpr_log2 = 0;
+    while ((1 << t.tpr_log2) < cols) ++t.tpr_log2;
+    if ((1 << t.tpr_log2) > NT) return false;
+    const int rpp = NT >> t.tpr_log2;
+    t.ksteps = g.ksteps;
+    t.mtiles = g.mtiles;
+    t.row_blocks = (p.Hout + t.TH - 1) / t.TH;
+    t.img_blocks = (p.N + t.NB - 1) / t.NB;
+    t.oc_blocks = g.KPG / MB;
+    const bool check_c = g.CPGp != g.CPG;   // padded channels are masked in the plan: one chunk only
+    const int cblks = g.CPGp / 4, taps = p.KH * p.KW;
+    int best = 0;
+    for (int d = check_c ? cblks : 1; d <= cblks; ++d) {
+        if (cblks % d) continue;
+        const int CK = 4 * d;
+        const int wsl = (c.MI * c.WM * d * taps * 16 + NT - 1) / NT;
+        const size_t in_f = (size_t)CK * t.PLANE, w_f = (size_t)wsl * NT * 4;
+        if (2 * (in_f + w_f + 4) * sizeof(float) > (size_t)kLdsBudget16) continue;
+        if ((CK * t.NB * t.IHt + rpp - 1) / rpp > kTmax16) continue;
+        if (wsl > kWmax16) continue;
+        best = d;
+    }
+    if (!best) return false;
+    t.CK = 4 * best;
+    t.nchunks = cblks / best;
+    t.m_IHt = div_magic(t.IHt);
+    t.m_NB = div_magic(t.NB);
+    t.m_ppi = div_magic(t.TH * p.Wout);
+    t.m_Wout = div_magic(p.Wout);
+    t.m_rowb = div_magic(t.row_blocks);
+    t.m_ocb = div_magic(t.oc_blocks);
+    t.tasks = t.CK * t.NB * t.IHt;
+    t.xslots = (t.tasks + rpp - 1) / rpp;
+    t.wslots = (c.MI * c.WM * best * taps * 16 + NT - 1) / NT;
+    t.in_floats = t.CK * t.PLANE;
+    t.w_floats = t.wslots * NT * 4;
+    const double xb = (double)p.N * p.Cin * p.H * p.W * (p.in_bf16 ? 2 : 4);
+    const double yb = (double)p.N * p.Cout * p.Hout * p.Wout * 4;
+    const double wb = (double)p.groups * g.ksteps * g.mtiles * 256;
+    if (xb >= (double)kOob || yb >= (double)kOob || wb >= (double)kOob) return false;
+    t.x_bytes = (unsigned)xb;
+    t.y_bytes = (unsigned)yb;
+    t.w_bytes = (unsigned)wb;
+    if ((long)t.row_blocks * t.img_blocks > 2147483647L || p.groups * t.oc_blocks > 65535) return false;
+    if ((double)t.row_blocks * t.img_blocks * t.row_blocks >= 4.0e9 ||
+        (double)p.groups * t.oc_blocks * t.oc_blocks >= 4.0e9 || t.tasks >= 65536 || t.TH * p.Wout >= 65536)
+        return false;
+    *out = t;
+    return true;
+}
+
+// Picks the block shape: the largest one that still gives every CU two blocks,
+// else the one with the most blocks.
+bool plan16(const ConvParams &p, const PackGeom &g, int *cfg_idx, Tile16 *t_out) {
+    if (g.variant != kMfma16 || !p.wm || !shape_instantiated(p.KH, p.KW, p.stride)) return false;
+    static const char *force = std::getenv("GSPC_TILE16");
+    if (force) {
+        const int i = std::atoi(force);
+        if (i >= 0 && i < kNumCfg16 && plan16_cfg(p, g, kCfg16[i], t_out)) {
+            *cfg_idx = i;
+            return true;
+        }
+    }
+    int best = -1;
+    long best_blocks = -1;
+    Tile16 bt{};
+    for (int i = 0; i < kNumCfg16; ++i) {
+        Tile16 t;
+        if (!plan16_cfg(p, g, kCfg16[i], &t)) continue;
+        const long blocks = (long)t.row_blocks * t.img_blocks * t.oc_blocks * p.groups;
+        if (blocks >= 4 * kNumCU) {
+            *cfg_idx = i;
+            *t_out = t;
+            return true;
+        }
+        if (blocks > best_blocks) {
+            best_blocks = blocks;
+            best = i;
+            bt = t;
+        }
+    }
+    if (best < 0) return false;
+    *cfg_idx = best;
+    *t_out = bt;
+    return true;
+}
+
+template <int MI, int NI, int WM, int WP, int KH, int KW, int S, typename TIN>
+hipError_t launch16_inst(const ConvParams &p, const Tile16 &t, hipStream_t s) {
+    const size_t lds = 2 * ((size_t)t.in_floats + t.w_floats + 4) * sizeof(float);
     dim3 grid(t.row_blocks * t.img_blocks, p.groups * t.oc_blocks);
-    hipLaunchKernelGGL((conv_mfma<VAR, MI, NI, WM, WP, KH, KW, S, TIN>), grid, dim3(64 * WM * WP), lds, s,
-                       p, t);
+    auto kern = conv_mfma16<MI, NI, WM, WP, KH, KW, S, TIN>;
+    if (lds > 64 * 1024) {
+        static thread_local size_t allowed = 0;   // per instantiation and thread
+        if (lds > allowed) {
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsMax);
+            if (e != hipSuccess) return e;
+            allowed = kLdsMax;
+        }
+    }
+    hipLaunchKernelGGL(kern, grid, dim3(64 * WM * WP), lds, s, p, t);
     return hipGetLastError();
 }
 
-template <int VAR, int MI, int NI, int WM, int WP, typename TIN>
-hipError_t launch_shape(const ConvParams &p, const MfmaTile &t, hipStream_t s) {
-    if (p.KH == 3 && p.stride == 1) return launch_inst<VAR, MI, NI, WM, WP, 3, 3, 1, TIN>(p, t, s);
-    if (p.KH == 3 && p.stride == 2) return launch_inst<VAR, MI, NI, WM, WP, 3, 3, 2, TIN>(p, t, s);
-    if (p.KH == 1 && p.stride == 1) return launch_inst<VAR, MI, NI, WM, WP, 1, 1, 1, TIN>(p, t, s);
-    if (p.KH == 1 && p.stride == 2) return launch_inst<VAR, MI, NI, WM, WP, 1, 1, 2, TIN>(p, t, s);
-    if (p.KH == 7 && p.stride == 2) return launch_inst<VAR, MI, NI, WM, WP, 7, 7, 2, TIN>(p, t, s);
+template <int MI, int NI, int WM, int WP, typename TIN>
+hipError_t launch16_shape(const ConvParams &p, const Tile16 &t, hipStream_t s) {
+    if (p.KH == 3 && p.stride == 1) return launch16_inst<MI, NI, WM, WP, 3, 3, 1, TIN>(p, t, s);
+    if (p.KH == 3 && p.stride == 2) return launch16_inst<MI, NI, WM, WP, 3, 3, 2, TIN>(p, t, s);
+    if (p.KH == 1 && p.stride == 1) return launch16_inst<MI, NI, WM, WP, 1, 1, 1, TIN>(p, t, s);
+    if (p.KH == 1 && p.stride == 2) return launch16_inst<MI, NI, WM, WP, 1, 1, 2, TIN>(p, t, s);
+    if (p.KH == 7 && p.stride == 2) return launch16_inst<MI, NI, WM, WP, 7, 7, 2, TIN>(p, t, s);
     return hipErrorNotSupported;
 }
 
 template <typename TIN>
-hipError_t launch_cfg(const Cfg &c, const ConvParams &p, const MfmaTile &t, hipStream_t s,
-                      const char **name) {
-#define GSPC_CFG(V, MI_, NI_, WM_, WP_, NAME)                                      \
-    if (c.VAR == V && c.MI == MI_ && c.NI == NI_ && c.WM == WM_ && c.WP == WP_) { \
-        *name = NAME;                                                              \
-        return launch_shape<V, MI_, NI_, WM_, WP_, TIN>(p, t, s);                  \
+hipError_t launch16_cfg(int i, const ConvParams &p, const Tile16 &t, hipStream_t s) {
+    switch (i) {
+    case 0: return launch16_shape<4, 4, 1, 4, TIN>(p, t, s);
+    case 1: return launch16_shape<2, 4, 1, 4, TIN>(p, t, s);
+    case 2: return launch16_shape<4, 2, 1, 4, TIN>(p, t, s);
+    case 3: return launch16_shape<2, 2, 1, 4, TIN>(p, t, s);
+    case 4: return launch16_shape<1, 4, 1, 4, TIN>(p, t, s);
+    case 5: return launch16_shape<2, 2, 2, 2, TIN>(p, t, s);
+    case 6: return launch16_shape<1, 2, 1, 4, TIN>(p, t, s);
+    case 7: return launch16_shape<2, 1, 1, 4, TIN>(p, t, s);
+    case 8: return launch16_shape<1, 1, 1, 4, TIN>(p, t, s);
     }
-    GSPC_CFG(32, 2, 2, 2, 2, "conv_mfma<32x32x2,128x128>")
-    GSPC_CFG(32, 2, 2, 1, 4, "conv_mfma<32x32x2,64x256>")
-    GSPC_CFG(32, 1, 2, 1, 4, "conv_mfma<32x32x2,32x256>")
-    GSPC_CFG(16, 1, 4, 1, 4, "conv_mfma<16x16x4,16x256>")
-    GSPC_CFG(4, 2, 1, 1, 4, "conv_mfma<4x4x1,8x256>")
-    GSPC_CFG(4, 1, 1, 1, 4, "conv_mfma<4x4x1,4x256>")
-#undef GSPC_CFG
     return hipErrorNotSupported;
+}
+
+// Planning costs microseconds of host time, so its outcome is remembered per
+// thread, keyed by everything it depends on.
+struct PlanKey {
+    int v[14];
+    bool operator==(const PlanKey &o) const { return std::memcmp(v, o.v, sizeof(v)) == 0; }
+};
+struct PlanKeyHash {
+    size_t operator()(const PlanKey &k) const {
+        uint64_t h = 1469598103934665603ull;
+        for (int x : k.v) h = (h ^ (uint32_t)x) * 1099511628211ull;
+        return (size_t)h;
+    }
+};
+struct Plan {
+    int kind;  // 0 none, 16, 4
+    int idx;
+    Tile16 t16;
+    Mfma4Plan p4;
+};
+
+const Plan &get_plan(const ConvParams &p, const PackGeom &g) {
+    thread_local std::unordered_map<PlanKey, Plan, PlanKeyHash> cache;
+    PlanKey k{{p.N, p.Cin, p.H, p.W, p.Cout, p.KH, p.KW, p.stride, p.pad, p.groups, p.in_bf16,
+               g.variant, p.wm != nullptr, 0}};
+    auto it = cache.find(k);
+    if (it != cache.end()) return it->second;
+    Plan pl{};
+    if (plan16(p, g, &pl.idx, &pl.t16)) pl.kind = 16;
+    else if (plan_mfma4(p, g, &pl.p4)) pl.kind = 4;
+    return cache.emplace(k, pl).first->second;
 }
 
 }  // namespace
 
-bool mfma_supported(const ConvParams &p, const PackGeom &g) {
-    Cfg c;
-    MfmaTile t;
-    return plan(p, g, &c, &t);
-}
+bool mfma_supported(const ConvParams &p, const PackGeom &g) { return get_plan(p, g).kind != 0; }
 
 hipError_t launch_mfma(const ConvParams &p, const PackGeom &g, hipStream_t s, const char **name) {
-    Cfg c;
-    MfmaTile t;
-    if (!plan(p, g, &c, &t)) return hipErrorNotSupported;
-    return p.in_bf16 ? launch_cfg<uint16_t>(c, p, t, s, name) : launch_cfg<float>(c, p, t, s, name);
+    const Plan &pl = get_plan(p, g);
+    if (pl.kind == 16) {
+        *name = kCfg16[pl.idx].name;
+        return p.in_bf16 ? launch16_cfg<uint16_t>(pl.idx, p, pl.t16, s) : launch16_cfg<float>(pl.idx, p, pl.t16, s);
+    }
+    if (pl.kind == 4) return launch_mfma4(p, pl.p4, s, name);
+    return hipErrorNotSupported;
 }
 
 }  // namespace gspc

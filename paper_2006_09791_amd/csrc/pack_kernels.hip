@@ -44,14 +44,14 @@ __global__ void pack_mfma_kernel(const float *__restrict__ w, float *__restrict_
     if (d >= total) return;
     const int lane = (int)(d % 64);
     size_t r = d / 64;
-    const int ks = (int)(r % a.ksteps);
-    r /= a.ksteps;
     const int mt = (int)(r % a.mtiles);
-    const int j = (int)(r / a.mtiles);
+    r /= a.mtiles;
+    const int ks = (int)(r % a.ksteps);
+    const int j = (int)(r / a.ksteps);
     const int taps = a.KH * a.KW;
     const int cblk = ks / taps, tap = ks % taps;
     const int oc_in = lane % a.variant;
-    const int sub = a.variant == 4 ? 0 : lane / a.variant;
+    const int sub = lane / a.variant;
     const int c = cblk * a.ksub + sub;
     float v = 0.f;
     if (c < a.CPG) {
@@ -77,9 +77,9 @@ __global__ void unpack_kernel(const float *__restrict__ sec, float *__restrict__
     const int c = k / taps, tap = k % taps;
     const int mt = o / a.variant, oc_in = o % a.variant;
     const int cblk = c / a.ksub, sub = c % a.ksub;
-    const int lane = (a.variant == 4 ? 0 : sub * a.variant) + oc_in;
+    const int lane = sub * a.variant + oc_in;
     const int ks = cblk * taps + tap;
-    w[d] = sec[(((size_t)j * a.mtiles + mt) * a.ksteps + ks) * 64 + lane];
+    w[d] = sec[(((size_t)j * a.ksteps + ks) * a.mtiles + mt) * 64 + lane];
 }
 
 __global__ void cast_bf16_kernel(const float *__restrict__ in, uint16_t *__restrict__ out,
@@ -112,7 +112,7 @@ hipError_t launch_pack_weights(const float *w, const gspc_packed *h, hipStream_t
                        nd, nd_gap);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    if (h->geom.variant != kMfmaNone) {
+    if (h->geom.mfma_bytes) {
         float *msec = reinterpret_cast<float *>(static_cast<char *>(h->dev) + h->geom.mfma_offset);
         const size_t nm = h->geom.mfma_bytes / sizeof(float);
         hipLaunchKernelGGL(pack_mfma_kernel, dim3(blocks_for(nm, 256)), dim3(256), 0, s, w, msec, a, nm);
