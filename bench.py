@@ -66,6 +66,10 @@ def main():
         return 2
     dev = torch.device("cuda:0")
     b.load()                       # raises if libgspc.so is missing: no fallback
+    # All work goes to one non-default stream (default priority): the chain
+    # runner records its launches into HIP graphs only off the null stream.
+    stream = torch.cuda.Stream()
+    torch.cuda.set_stream(stream)
     b.gspc_set_stream()
 
     # ---- build the five chains, everything resident on the device ----------
@@ -127,7 +131,10 @@ def main():
                     continue
                 seen[key] = [l, 1]
             for l, count in seen.values():
-                one = b.LayerChain([l], packed, bufs)
+                # the same layer `inner` times in one recorded chain: back-to-back
+                # launches with no host in the loop
+                inner = 10
+                one = b.LayerChain([l] * inner, packed, bufs)
                 b.gspc_run_layer_chain(one)
                 name = b.gspc_last_kernel()
                 e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -137,7 +144,7 @@ def main():
                     b.gspc_run_layer_chain(one)
                 e1.record()
                 torch.cuda.synchronize()
-                dur = e0.elapsed_time(e1) / reps * 1e-3
+                dur = e0.elapsed_time(e1) / (reps * inner) * 1e-3
                 flops, nbytes = layer_flops_bytes(l)
                 k = kernels.setdefault(name, {"time": 0.0, "flops": 0.0, "bytes": 0.0, "launches": 0,
                                               "compute_bound": False})

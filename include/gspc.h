@@ -164,6 +164,14 @@ typedef struct gspc_layer {
     const gspc_packed_t *w;
 } gspc_layer_t;
 
+/* Layer chains without per-layer timing are, by default, recorded into a HIP
+ * graph on first use (keyed by the layer list, the buffer addresses and the
+ * stream) and replayed on later calls; this needs a stream other than the null
+ * stream and is skipped while the caller is itself capturing the stream.  The
+ * recorded graphs belong to the calling thread; gspc_set_graph_mode(0) turns
+ * the feature off and releases them, gspc_set_graph_mode(1) turns it back on. */
+int gspc_set_graph_mode(int on);
+
 /* Runs the steps in order on the selected stream.  act_bufs[i] (dev) holds
  * act_bytes[i] bytes; every step is validated against those sizes before
  * anything is launched (GSPC_ERR_SPACE / GSPC_ERR_ARG).  A CONV whose handle

@@ -5,6 +5,7 @@
 #include <cstdlib>
 #include <cstring>
 #include <new>
+#include <unordered_map>
 #include <vector>
 
 #include "gspc_internal.h"
@@ -16,6 +17,47 @@ thread_local char t_error[512] = "";
 thread_local int t_force_path = GSPC_PATH_AUTO;
 thread_local int t_last_path = GSPC_PATH_AUTO;
 thread_local const char *t_last_kernel = "";
+thread_local int t_graph_mode = 1;
+
+// Recorded layer chains, per thread, keyed by everything a replay depends on.
+struct ChainGraph {
+    hipGraph_t graph;
+    hipGraphExec_t exec;
+};
+thread_local std::unordered_map<uint64_t, ChainGraph> t_graphs;
+
+void clear_graphs() {
+    for (auto &kv : t_graphs) {
+        (void)hipGraphExecDestroy(kv.second.exec);
+        (void)hipGraphDestroy(kv.second.graph);
+    }
+    t_graphs.clear();
+}
+
+uint64_t fnv(uint64_t h, const void *data, size_t n) {
+    const unsigned char *b = static_cast<const unsigned char *>(data);
+    for (size_t i = 0; i < n; ++i) h = (h ^ b[i]) * 1099511628211ull;
+    return h;
+}
+
+uint64_t chain_key(const gspc_layer_t *layers, int n_layers, void *const *bufs, int n_bufs,
+                   hipStream_t stream, int force_path) {
+    uint64_t h = 1469598103934665603ull;
+    for (int i = 0; i < n_layers; ++i) {
+        const gspc_layer_t &L = layers[i];
+        const int f[15] = {L.op, L.src, L.src2, L.dst, L.N, L.Cin, L.H, L.W, L.Cout, L.KH, L.KW,
+                           L.stride, L.pad, L.groups, L.flags};
+        h = fnv(h, f, sizeof(f));
+        if (L.op == GSPC_OP_CONV && L.w) {
+            h = fnv(h, &L.w->dev, sizeof(L.w->dev));
+            h = fnv(h, &L.w->dtype, sizeof(L.w->dtype));
+        }
+    }
+    h = fnv(h, bufs, sizeof(void *) * n_bufs);
+    h = fnv(h, &stream, sizeof(stream));
+    h = fnv(h, &force_path, sizeof(force_path));
+    return h;
+}
 
 int fail(int code, const char *fmt, ...) {
     va_list ap;
@@ -264,6 +306,12 @@ int gspc_force_path(int path) {
     return GSPC_OK;
 }
 
+int gspc_set_graph_mode(int on) {
+    t_graph_mode = on ? 1 : 0;
+    if (!on) clear_graphs();
+    return GSPC_OK;
+}
+
 int gspc_last_path(void) { return t_last_path; }
 const char *gspc_last_kernel(void) { return t_last_kernel; }
 
@@ -332,25 +380,16 @@ int gspc_run_layer_chain(const gspc_layer_t *layers, int n_layers, void *const *
         }
     }
 
-    // Pass 2: launch.
-    std::vector<hipEvent_t> ev;
-    if (per_layer_ms) {
-        ev.resize(n_layers + 1);
-        for (auto &e : ev) {
-            hipError_t er = hipEventCreate(&e);
-            if (er != hipSuccess) return hip_fail(er, "hipEventCreate");
-        }
-        (void)hipEventRecord(ev[0], t_stream);
-    }
-    int rc = GSPC_OK;
-    for (int i = 0; i < n_layers && rc == GSPC_OK; ++i) {
+    // Pass 2: launch.  Without per-layer timing, and on a capturable stream,
+    // the launches are recorded once into a HIP graph and replayed afterwards:
+    // at batch 1 the kernels are shorter than the host's launch cost.
+    auto launch_step = [&](int i) -> int {
         const gspc_layer_t &L = layers[i];
         const size_t elems = (size_t)L.N * L.Cin * L.H * L.W;
         hipError_t e = hipSuccess;
         switch (L.op) {
         case GSPC_OP_CONV:
-            rc = dispatch_conv(params[i], L.w);
-            break;
+            return dispatch_conv(params[i], L.w);
         case GSPC_OP_MAXPOOL:
             e = gspc::launch_maxpool(static_cast<const float *>(act_bufs[L.src]),
                                      static_cast<float *>(act_bufs[L.dst]), L.N, L.Cin, L.H, L.W,
@@ -368,10 +407,63 @@ int gspc_run_layer_chain(const gspc_layer_t *layers, int n_layers, void *const *
                                   static_cast<float *>(act_bufs[L.dst]), elems, t_stream);
             break;
         }
-        if (e != hipSuccess) rc = hip_fail(e, "chain op launch");
-        if (per_layer_ms) (void)hipEventRecord(ev[i + 1], t_stream);
+        return e == hipSuccess ? GSPC_OK : hip_fail(e, "chain op launch");
+    };
+
+    if (!per_layer_ms) {
+        hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+        const bool try_graph = t_graph_mode && t_stream != nullptr && n_layers > 1 &&
+                               hipStreamIsCapturing(t_stream, &cap) == hipSuccess &&
+                               cap == hipStreamCaptureStatusNone;
+        if (try_graph) {
+            const uint64_t key = chain_key(layers, n_layers, act_bufs, n_bufs, t_stream, t_force_path);
+            auto it = t_graphs.find(key);
+            if (it == t_graphs.end()) {
+                hipGraph_t graph = nullptr;
+                hipGraphExec_t exec = nullptr;
+                if (hipStreamBeginCapture(t_stream, hipStreamCaptureModeThreadLocal) == hipSuccess) {
+                    int rc2 = GSPC_OK;
+                    for (int i = 0; i < n_layers && rc2 == GSPC_OK; ++i) rc2 = launch_step(i);
+                    const hipError_t ee = hipStreamEndCapture(t_stream, &graph);
+                    if (rc2 != GSPC_OK) {
+                        if (graph) (void)hipGraphDestroy(graph);
+                        return rc2;
+                    }
+                    if (ee == hipSuccess && graph &&
+                        hipGraphInstantiate(&exec, graph, nullptr, nullptr, 0) == hipSuccess) {
+                        if (t_graphs.size() >= 64) clear_graphs();
+                        it = t_graphs.emplace(key, ChainGraph{graph, exec}).first;
+                    } else {
+                        if (graph) (void)hipGraphDestroy(graph);
+                        (void)hipGetLastError();
+                    }
+                } else {
+                    (void)hipGetLastError();
+                }
+            }
+            if (it != t_graphs.end()) {
+                const hipError_t e = hipGraphLaunch(it->second.exec, t_stream);
+                if (e != hipSuccess) return hip_fail(e, "hipGraphLaunch");
+                return GSPC_OK;
+            }
+        }
+        int rc = GSPC_OK;
+        for (int i = 0; i < n_layers && rc == GSPC_OK; ++i) rc = launch_step(i);
+        return rc;
     }
-    if (per_layer_ms) {
+
+    std::vector<hipEvent_t> ev(n_layers + 1);
+    for (auto &e : ev) {
+        hipError_t er = hipEventCreate(&e);
+        if (er != hipSuccess) return hip_fail(er, "hipEventCreate");
+    }
+    (void)hipEventRecord(ev[0], t_stream);
+    int rc = GSPC_OK;
+    for (int i = 0; i < n_layers && rc == GSPC_OK; ++i) {
+        rc = launch_step(i);
+        (void)hipEventRecord(ev[i + 1], t_stream);
+    }
+    {
         hipError_t e = hipStreamSynchronize(t_stream);
         if (e != hipSuccess && rc == GSPC_OK) rc = hip_fail(e, "hipStreamSynchronize");
         for (int i = 0; i < n_layers; ++i) {

@@ -27,8 +27,22 @@ def oracle_chain(chain, x0, weights, threads=8):
     return oracle.run_chain(chain.layers, len(chain.buf_elems), x0, weights, threads=threads)
 
 
+_side_stream = None
+
+
+def side_stream():
+    """A non-default torch stream (default priority): layer chains are only
+    recorded into HIP graphs on a stream other than the null stream."""
+    global _side_stream
+    import torch
+    if _side_stream is None:
+        _side_stream = torch.cuda.Stream()
+    return _side_stream
+
+
 def gpu_chain(chain, x0, weights, dtype=None):
-    """Packs weights, allocates buffers and returns (LayerChain, buffers)."""
+    """Packs weights, allocates buffers and returns (LayerChain, buffers).
+    Setup runs on torch's current stream and is synchronised before return."""
     import torch
     from paper_2006_09791_amd import binding as b
     dev = torch.device("cuda:0")
@@ -37,4 +51,5 @@ def gpu_chain(chain, x0, weights, dtype=None):
               for w, g in zip(weights, chain.weight_groups)]
     bufs = [torch.empty(max(n, 1), dtype=torch.float32, device=dev) for n in chain.buf_elems]
     bufs[0].copy_(torch.from_numpy(np.ascontiguousarray(x0, dtype=np.float32)).reshape(-1))
+    torch.cuda.synchronize()
     return b.LayerChain(chain.layers, packed, bufs), bufs

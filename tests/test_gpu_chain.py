@@ -2,7 +2,7 @@
 import numpy as np
 import pytest
 
-from helpers import TOL_F32, gpu_chain, oracle_chain, rel_err
+from helpers import TOL_F32, gpu_chain, oracle_chain, rel_err, side_stream
 from paper_2006_09791_amd import workloads as wl
 
 pytestmark = pytest.mark.gpu
@@ -18,11 +18,20 @@ def _run(chain, config_id, seed):
     assert len(ms) == len(chain.layers) and all(m >= 0 for m in ms)
     n_out = int(np.prod(chain.out_shape))
     got = bufs[chain.out_buf][:n_out].cpu().numpy().reshape(chain.out_shape)
-    # asynchronous form gives the same bits
-    b.gspc_run_layer_chain(lc)
-    torch.cuda.synchronize()
-    again = bufs[chain.out_buf][:n_out].cpu().numpy().reshape(chain.out_shape)
-    assert np.array_equal(got, again)
+    # The asynchronous form on a side stream is recorded into a HIP graph on
+    # its first call and replayed afterwards: every replay must give the same
+    # bits as the eager run, with unrelated eager work in between.
+    with torch.cuda.stream(side_stream()):
+        b.gspc_set_stream()
+        for rep in range(4):
+            bufs[chain.out_buf].zero_()
+            b.gspc_run_layer_chain(lc)
+            torch.cuda.synchronize()
+            again = bufs[chain.out_buf][:n_out].cpu().numpy().reshape(chain.out_shape)
+            assert np.array_equal(got, again), f"graph replay {rep} differs from the eager run"
+            scratch = torch.randn(1 << 16, device="cuda")
+            (scratch * 2).sum().item()
+    b.gspc_set_stream()
     ref = oracle_chain(chain, x0, weights)[chain.out_buf]
     return got, ref
 
@@ -71,3 +80,26 @@ def test_chain_validation_precedes_launch():
     assert e.value.code == -6
     torch.cuda.synchronize()
     assert float(bufs[1].min()) == 123.0    # first layer was not launched either
+
+
+def test_graph_mode_off_matches():
+    import torch
+    from paper_2006_09791_amd import binding as b
+    chain = wl.wrn_chain(2, 8)
+    x0 = wl.make_input(chain.input_shape, 5)
+    weights = chain.make_weights(2)
+    lc, bufs = gpu_chain(chain, x0, weights)
+    n_out = int(np.prod(chain.out_shape))
+    outs = []
+    with torch.cuda.stream(side_stream()):
+        b.gspc_set_stream()
+        for on in (1, 0, 1):
+            b.gspc_set_graph_mode(on)
+            bufs[chain.out_buf].zero_()
+            b.gspc_run_layer_chain(lc)
+            b.gspc_run_layer_chain(lc)
+            torch.cuda.synchronize()
+            outs.append(bufs[chain.out_buf][:n_out].cpu().numpy())
+    b.gspc_set_graph_mode(1)
+    b.gspc_set_stream()
+    assert np.array_equal(outs[0], outs[1]) and np.array_equal(outs[1], outs[2])
