@@ -49,6 +49,11 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-roofline", action="store_true")
+    ap.add_argument("--traffic-probe", action="store_true",
+                    help="first run a plain 256 MiB device copy three times: the known-size kernel "
+                         "against which rocprofv3's FETCH_SIZE / WRITE_SIZE counters are scaled")
+    ap.add_argument("--serial", action="store_true",
+                    help="run the five chains of a step one after the other on one stream")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (--gpus 1); "
@@ -72,6 +77,14 @@ def main():
     torch.cuda.set_stream(stream)
     b.gspc_set_stream()
 
+    if args.traffic_probe:
+        src = torch.ones(64 * 1024 * 1024, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            torch.mul(src, 1.0, out=dst)      # one elementwise kernel: reads and writes 256 MiB
+        torch.cuda.synchronize()
+        del src, dst
+
     # ---- build the five chains, everything resident on the device ----------
     chains, lcs, keep = [], [], []
     for g in GROUPS:
@@ -87,9 +100,17 @@ def main():
         keep.append((packed, bufs))
     macs_step = sum(ch.macs() for ch in chains)
 
+    # The five chains of a step are independent of each other, so each runs on
+    # a stream of its own (all at default priority) and the GPU overlaps them.
+    streams = [stream] + [torch.cuda.Stream() for _ in lcs[1:]]
+    if args.serial:
+        streams = [stream] * len(lcs)
+
     def step():
-        for lc in lcs:
+        for lc, st in zip(lcs, streams):
+            b.gspc_set_stream(st)
             b.gspc_run_layer_chain(lc)
+        b.gspc_set_stream(stream)
 
     for _ in range(args.warmup):
         step()

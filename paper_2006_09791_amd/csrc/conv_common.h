@@ -1,6 +1,10 @@
 // Device and host helpers shared by the convolution kernels of libgspc.
 #pragma once
 
+#include <mutex>
+#include <set>
+#include <string>
+
 #include "gspc_internal.h"
 
 namespace gspc {
@@ -41,7 +45,17 @@ template <> __device__ __forceinline__ f32x4 buf_load_in<uint16_t>(__amdgpu_buff
 }
 
 
-// ---- host-side planning helpers ---------------------------------------------
+// ---- host-side helpers --------------------------------------------------------
+// Kernel names are reported as the template arguments of the instance that ran,
+// so they can be matched one to one with a profiler's kernel names.  The
+// returned pointer stays valid for the life of the process.
+inline const char *intern_name(const std::string &s) {
+    static std::mutex mu;
+    static std::set<std::string> names;
+    std::lock_guard<std::mutex> lock(mu);
+    return names.insert(s).first->c_str();
+}
+
 constexpr int kNumCU = 256;
 
 inline unsigned div_magic(int d) { return d > 1 ? (unsigned)(0xffffffffu / (unsigned)d + 1u) : 0u; }

@@ -247,7 +247,9 @@ hipError_t launch_direct(const ConvParams &p, hipStream_t s, const char **name) 
     static const bool no_small = std::getenv("GSPC_NO_SMALL") != nullptr;   // tuning aid
     TileS ts;
     if (!no_small && plan_small(p, &ts)) {
-        *name = p.CPG == 1 && p.KPG == 1 ? "conv_direct_small<depthwise>" : "conv_direct_small";
+        *name = intern_name("conv_direct_small<" + std::to_string(p.CPG) + "," + std::to_string(p.KPG) + "," +
+                            std::to_string(p.stride) + "," + std::to_string(p.stride == 1 ? 4 : 2) +
+                            (p.in_bf16 ? ",bf16>" : ",f32>"));
         return p.in_bf16 ? launch_small<uint16_t>(p, ts, s) : launch_small<float>(p, ts, s);
     }
     const bool oct8 = p.KPGd % 8 == 0;

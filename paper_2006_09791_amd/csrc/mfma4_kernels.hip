@@ -299,26 +299,19 @@ bool plan_mfma4(const ConvParams &p, const PackGeom &g, Mfma4Plan *out) {
     const int MT = g.KPG / 4;
     if (!inst_exists(g.CPG, MT)) return false;
     static const char *force = std::getenv("GSPC_TILE4");
-    // Most pixel runs per wave (more independent accumulators, fewer weight
-    // loads) that still leaves two blocks per CU.
+    // Most pixel runs per wave (more independent accumulators, fewer filter-bank
+    // loads, less halo re-staging) while a block still works on a single image:
+    // images share nothing, so packing several into a block only costs blocks.
     int chosen = 0;
     Tile4 best{};
-    long best_blocks = -1;
     for (int nt : {4, 2, 1}) {
         Tile4 t;
         if (force && std::atoi(force) != nt) continue;
         if (!plan4_tile(p, g, nt, &t)) continue;
         const long blocks = (long)t.row_blocks * t.img_blocks * p.groups;
-        if (blocks >= 2 * kNumCU) {
-            chosen = nt;
-            best = t;
-            break;
-        }
-        if (blocks > best_blocks) {
-            best_blocks = blocks;
-            chosen = nt;
-            best = t;
-        }
+        chosen = nt;
+        best = t;
+        if (t.NB == 1 && blocks >= kNumCU / 2) break;
     }
     if (!chosen) return false;
     out->inst = chosen;
@@ -329,9 +322,9 @@ bool plan_mfma4(const ConvParams &p, const PackGeom &g, Mfma4Plan *out) {
 hipError_t launch_mfma4(const ConvParams &p, const Mfma4Plan &plan, hipStream_t s, const char **name) {
     Tile4 t;
     std::memcpy(&t, plan.data, sizeof(t));
-    static const char *names[] = {"", "conv_mfma4r<64px/wave>", "conv_mfma4r<128px/wave>", "",
-                                  "conv_mfma4r<256px/wave>"};
-    *name = names[plan.inst];
+    *name = intern_name("conv_mfma4r<" + std::to_string(p.CPG) + "," + std::to_string(p.KPG / 4) + "," +
+                        std::to_string(plan.inst) + "," + std::to_string(p.stride) +
+                        (p.in_bf16 ? ",bf16>" : ",f32>"));
     const int MT = p.KPG / 4;
     return p.in_bf16 ? launch4_any<uint16_t>(p.CPG, MT, plan.inst, p.stride, p, t, s)
                      : launch4_any<float>(p.CPG, MT, plan.inst, p.stride, p, t, s);

@@ -498,7 +498,11 @@ bool mfma_supported(const ConvParams &p, const PackGeom &g) { return get_plan(p,
 hipError_t launch_mfma(const ConvParams &p, const PackGeom &g, hipStream_t s, const char **name) {
     const Plan &pl = get_plan(p, g);
     if (pl.kind == 16) {
-        *name = kCfg16[pl.idx].name;
+        const Cfg16 &c = kCfg16[pl.idx];
+        *name = intern_name("conv_mfma16<" + std::to_string(c.MI) + "," + std::to_string(c.NI) + "," +
+                            std::to_string(c.WM) + "," + std::to_string(c.WP) + "," + std::to_string(p.KH) +
+                            "," + std::to_string(p.KW) + "," + std::to_string(p.stride) +
+                            (p.in_bf16 ? ",bf16>" : ",f32>"));
         return p.in_bf16 ? launch16_cfg<uint16_t>(pl.idx, p, pl.t16, s) : launch16_cfg<float>(pl.idx, p, pl.t16, s);
     }
     if (pl.kind == 4) return launch_mfma4(p, pl.p4, s, name);
