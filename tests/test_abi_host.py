@@ -1,0 +1,107 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports
+every function include/gspc.h declares, and rejects bad arguments before any
+GPU work (all these calls return before the first HIP call)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2006_09791_amd import binding as b
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "gspc.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(gspc_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = b.load()
+    names = declared_functions()
+    assert len(names) >= 16
+    for n in names:
+        assert hasattr(lib, n), f"{n} declared in gspc.h but not exported"
+    assert set(names) == set(b.EXPORTS)
+
+
+def test_version_and_output_dims():
+    assert b.gspc_version() == 1
+    assert b.gspc_output_dims(32, 32, 3, 3, 1, 1) == (32, 32)
+    assert b.gspc_output_dims(7, 7, 3, 3, 2, 1) == (4, 4)
+    assert b.gspc_output_dims(224, 224, 7, 7, 2, 3) == (112, 112)
+    with pytest.raises(b.GspcError) as e:
+        b.gspc_output_dims(2, 2, 5, 5, 1, 0)
+    assert e.value.code == -2
+    with pytest.raises(b.GspcError) as e:
+        b.gspc_output_dims(8, 8, 3, 3, 0, 1)
+    assert e.value.code == -2
+
+
+def test_layer_macs_is_eq2():
+    assert b.gspc_layer_macs(1, 64, 64, 3, 3, 32, 32, 4) == 9437184
+    assert b.gspc_layer_macs(2, 6, 4, 3, 3, 3, 2, 2) == 2 * 6 * 4 * 9 * 6 // 2
+    assert b.gspc_layer_macs(1, 0, 4, 3, 3, 3, 2, 2) == 0
+
+
+def test_packed_bytes_and_group_divisibility():
+    lib = b.load()
+    n = b.gspc_packed_weight_bytes(64, 64, 3, 3, 4)
+    assert n >= 64 * 16 * 9 * 4 and n % 4 == 0
+    # KPG = 16 carries a matrix-core section on top of the direct one
+    assert n > b.gspc_packed_weight_bytes(64, 8, 3, 3, 4)
+    assert lib.gspc_packed_weight_bytes(6, 4, 3, 3, 4, 0) == 0       # 6 % 4 != 0
+    assert "divisible" in b.gspc_last_error()
+    assert lib.gspc_packed_weight_bytes(8, 8, 3, 3, 2, 7) == 0       # unknown dtype
+    assert lib.gspc_packed_weight_bytes(8, 8, 0, 3, 2, 0) == 0
+
+
+def test_pack_and_conv_reject_bad_arguments_before_any_launch():
+    lib = b.load()
+    h = ctypes.c_void_p()
+    fake = ctypes.c_void_p(256 * 1024)          # never dereferenced: validation fails first
+    assert lib.gspc_pack_weights(None, 8, 8, 3, 3, 2, 0, fake, 1 << 20, ctypes.byref(h)) == -1
+    assert lib.gspc_pack_weights(fake, 8, 8, 3, 3, 3, 0, fake, 1 << 20, ctypes.byref(h)) == -3
+    assert lib.gspc_pack_weights(fake, 8, 8, 3, 3, 2, 5, fake, 1 << 20, ctypes.byref(h)) == -4
+    assert lib.gspc_pack_weights(fake, 8, 8, 3, 3, 2, 0, fake, 16, ctypes.byref(h)) == -6
+    assert lib.gspc_pack_weights(fake, 8, 8, 3, 3, 2, 0, ctypes.c_void_p(256 * 1024 + 4), 1 << 20,
+                                 ctypes.byref(h)) == -8
+    assert lib.gspc_conv2d_grouped(fake, None, 1, 8, 4, 4, 8, 3, 3, 1, 1, 2, fake) == -1
+    assert lib.gspc_unpack_weights(None, 0, fake) == -1
+    assert lib.gspc_packed_info(None, None, None, None, None, None, None, None) == -1
+    assert lib.gspc_pack_input_bf16(None, 4, fake) == -1
+    assert lib.gspc_force_path(9) == -8
+    assert lib.gspc_force_path(-1) == 0
+    lib.gspc_packed_free(None)
+
+
+def test_chain_rejects_bad_arguments_before_any_launch():
+    lib = b.load()
+    layers = (b.GspcLayer * 1)()
+    bufs = (ctypes.c_void_p * 2)(256 * 1024, 512 * 1024)
+    sizes = (ctypes.c_size_t * 2)(1024, 1024)
+    assert lib.gspc_run_layer_chain(None, 1, bufs, sizes, 2, None) == -1
+    assert lib.gspc_run_layer_chain(layers, 0, bufs, sizes, 2, None) == -8
+    L = layers[0]
+    L.op, L.src, L.dst, L.src2 = b.OP_RELU, 0, 5, -1
+    L.N, L.Cin, L.H, L.W = 1, 4, 4, 4
+    assert lib.gspc_run_layer_chain(layers, 1, bufs, sizes, 2, None) == -8     # dst out of range
+    L.dst = 1
+    L.Cin = 4096
+    assert lib.gspc_run_layer_chain(layers, 1, bufs, sizes, 2, None) == -6     # buffer too small
+    L.Cin, L.op = 4, 77
+    assert lib.gspc_run_layer_chain(layers, 1, bufs, sizes, 2, None) == -8     # unknown op
+    L.op, L.w = b.OP_CONV, None
+    assert lib.gspc_run_layer_chain(layers, 1, bufs, sizes, 2, None) == -1     # conv without weights
+
+
+def test_product_path_does_not_import_the_oracle():
+    pkg = os.path.join(ROOT, "paper_2006_09791_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".cpp", ".h")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert not re.search(r"^\s*(import|from)\s+oracle|liboracle|oracle_conv|#include.*oracle",
+                                     text, flags=re.M), f"{f} reaches into the oracle"
