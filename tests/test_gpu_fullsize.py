@@ -1,0 +1,75 @@
+"""Parity at the benchmark's full sizes, in the launch configuration bench.py
+times (same dispatcher, same tiles): the oracle recomputes sampled output
+channels of sampled images, whole planes at a time."""
+import numpy as np
+import pytest
+
+import oracle
+from helpers import TOL_BF16, TOL_F32, rel_err
+from paper_2006_09791_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+
+def _sampled_check(s, seed, dtype_bf16, n_img, n_oc, tol_same, tol_unrounded=None):
+    import torch
+    from paper_2006_09791_amd import binding as b
+    dev = torch.device("cuda:0")
+    b.gspc_set_stream()
+    b.gspc_force_path(b.PATH_AUTO)
+    x = wl.make_input((s.N, s.Cin, s.H, s.W), seed)
+    w = wl.make_weight(s.Cout, s.Cin // s.groups, s.KH, s.KW, seed)
+    dt = b.GSPC_BF16 if dtype_bf16 else b.GSPC_F32
+    pw = b.gspc_pack_weights(torch.from_numpy(w).to(dev), s.groups, dt)
+    xd = torch.from_numpy(x).to(dev)
+    if dtype_bf16:
+        xd = b.gspc_pack_input_bf16(xd)
+    y = b.gspc_conv2d_grouped(xd, pw, s.N, s.Cin, s.H, s.W, s.Cout, s.KH, s.KW, s.stride, s.pad,
+                              s.groups)
+    name = b.gspc_last_kernel()
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(seed + 1)
+    imgs = np.sort(rng.choice(s.N, size=min(n_img, s.N), replace=False))
+    # sampled filters: first, last, and random ones (hits several groups and tile positions)
+    ocs = np.unique(np.concatenate([[0, s.Cout - 1], rng.choice(s.Cout, size=n_oc, replace=False)]))
+    got = y[torch.from_numpy(imgs).to(dev)][:, torch.from_numpy(ocs).to(dev)].cpu().numpy()
+    assert np.isfinite(got).all()
+    xs, ws = x[imgs], w
+    if dtype_bf16:
+        _, xs_r = wl.round_to_bf16(xs)
+        _, ws_r = wl.round_to_bf16(ws)
+        ref = oracle.conv2d_grouped_channels(xs_r, ws_r, ocs, s.stride, s.pad, s.groups, threads=16)
+        assert rel_err(got, ref) < tol_same, (name, s)
+        if tol_unrounded:
+            ref2 = oracle.conv2d_grouped_channels(xs, ws, ocs, s.stride, s.pad, s.groups, threads=16)
+            assert rel_err(got, ref2) < tol_unrounded, (name, s)
+    else:
+        ref = oracle.conv2d_grouped_channels(xs, ws, ocs, s.stride, s.pad, s.groups, threads=16)
+        assert rel_err(got, ref) < tol_same, (name, s)
+    return name
+
+
+@pytest.mark.parametrize("g", [1, 2, 4, 8, 16])
+def test_wrn_layers_batch64_fp32(g):
+    for i, s in enumerate(wl.wrn_grouped_shapes(64, g)):
+        _sampled_check(s, wl.make_seed(2, 100 + i, g), False, n_img=3, n_oc=4, tol_same=TOL_F32)
+
+
+def test_wrn_stem_and_shortcuts_batch64_fp32():
+    S = wl.ConvShape
+    for i, s in enumerate([S(64, 3, 32, 32, 32, 3, 3, 1, 1, 1), S(64, 32, 32, 32, 64, 1, 1, 2, 0, 1),
+                           S(64, 64, 16, 16, 128, 1, 1, 2, 0, 1)]):
+        _sampled_check(s, wl.make_seed(2, 200 + i, 1), False, n_img=3, n_oc=4, tol_same=TOL_F32)
+
+
+@pytest.mark.parametrize("g", [2, 8, 32])
+def test_resnet34_layers_batch256_bf16(g):
+    for i, s in enumerate(wl.resnet34_grouped_shapes(256, g)):
+        _sampled_check(s, wl.make_seed(5, i, g), True, n_img=2, n_oc=4, tol_same=1e-4,
+                       tol_unrounded=TOL_BF16)
+
+
+def test_depthwise_batched_fp32():
+    # batched re-run of the MobileNet-shaped depthwise layers (HBM-bound kernel at a size that fills the GPU)
+    for i, (dw, _) in enumerate(wl.depthwise_pairs(32)):
+        _sampled_check(dw, wl.make_seed(4, 300 + i, dw.groups), False, n_img=2, n_oc=6, tol_same=TOL_F32)
