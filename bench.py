@@ -52,6 +52,9 @@ def main():
     ap.add_argument("--traffic-probe", action="store_true",
                     help="first run a plain 256 MiB device copy three times: the known-size kernel "
                          "against which rocprofv3's FETCH_SIZE / WRITE_SIZE counters are scaled")
+    ap.add_argument("--sweep", choices=["wrn", "resnet_bf16", "depthwise"],
+                    help="instead of the headline step, time every layer of a configuration family "
+                         "and print one JSON line with a row per layer")
     ap.add_argument("--serial", action="store_true",
                     help="run the five chains of a step one after the other on one stream")
     args = ap.parse_args()
@@ -76,6 +79,22 @@ def main():
     stream = torch.cuda.Stream()
     torch.cuda.set_stream(stream)
     b.gspc_set_stream()
+
+    if args.sweep:
+        from paper_2006_09791_amd import layer_timing
+        if args.sweep == "wrn":
+            shapes = [s for g in GROUPS for s in wl.wrn_grouped_shapes(BATCH, g)]
+            rows = layer_timing.time_layers(shapes, "f32")
+        elif args.sweep == "resnet_bf16":
+            shapes = [s for g in (2, 8, 32) for s in wl.resnet34_grouped_shapes(256, g)]
+            rows = layer_timing.time_layers(shapes, "bf16", inner=4, reps=5)
+        else:
+            # batched re-run of the MobileNet-shaped depthwise layers; buffer sets
+            # rotate so that every launch streams from HBM rather than from cache
+            shapes = [dw for dw, _ in wl.depthwise_pairs(256)]
+            rows = layer_timing.time_layers(shapes, "f32", inner=8, reps=5, rotate=4)
+        print(json.dumps({"sweep": args.sweep, "rows": rows}))
+        return 0
 
     if args.traffic_probe:
         src = torch.ones(64 * 1024 * 1024, dtype=torch.float32, device=dev)

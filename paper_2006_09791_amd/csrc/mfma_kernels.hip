@@ -87,15 +87,16 @@ __global__ __launch_bounds__(64 * WM * WP) void conv_mfma16(ConvParams p, Tile16
     const unsigned wvoff = (tid / (MIWM * 16)) * wrow + (tid % (MIWM * 16)) * 16;
     constexpr unsigned kWslot = (NT / (MIWM * 16));   // k-steps advanced per slot
     static_assert(NT % (MIWM * 16) == 0, "a slot must cover whole k-steps");
-    f32x4 pin[TMAX], pw[WMAX];
-    auto fetch_w = [&](int chunk) __attribute__((always_inline)) {
+    // Two register sets: a chunk is fetched two iterations before it is needed.
+    f32x4 pin0[TMAX], pw0[WMAX], pin1[TMAX], pw1[WMAX];
+    auto fetch_w = [&](int chunk, f32x4 (&pw)[WMAX]) __attribute__((always_inline)) {
         const unsigned so = wblk + chunk * kchunk * wrow;
 #pragma unroll
         for (int k = 0; k < WMAX; ++k)
             if (k < t.wslots)
                 pw[k] = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(rw, wvoff, so + k * kWslot * wrow, 0));
     };
-    fetch_w(0);
+    fetch_w(0, pw0);
 
     // ---- per-thread input staging plan (identical for every chunk) ---------
     const int rpp = NT >> t.tpr_log2;
@@ -116,13 +117,13 @@ __global__ __launch_bounds__(64 * WM * WP) void conv_mfma16(ConvParams p, Tile16
                 xoff[k] = (((n * p.Cin + j * p.CPG + c) * p.H + ih) * p.W + colv * vw) * ES;
         }
     }
-    auto fetch_x = [&](int chunk) __attribute__((always_inline)) {
+    auto fetch_x = [&](int chunk, f32x4 (&pin)[TMAX]) __attribute__((always_inline)) {
         const unsigned so = chunk * t.CK * HW * ES;
 #pragma unroll
         for (int k = 0; k < TMAX; ++k)
             if (k < t.xslots) pin[k] = buf_load_in<TIN>(rx, xoff[k], so, t.vec);
     };
-    auto commit = [&](int buf) __attribute__((always_inline)) {
+    auto commit = [&](int buf, const f32x4 (&pin)[TMAX], const f32x4 (&pw)[WMAX]) __attribute__((always_inline)) {
         char *bb = reinterpret_cast<char *>(smem) + buf * (buf_floats * 4);
 #pragma unroll
         for (int k = 0; k < TMAX; ++k) {
@@ -137,7 +138,11 @@ __global__ __launch_bounds__(64 * WM * WP) void conv_mfma16(ConvParams p, Tile16
             if (k < t.wslots) *reinterpret_cast<f32x4 *>(wb + k * NT * 16) = pw[k];
     };
     GSPC_STAMP(1)
-    fetch_x(0);
+    fetch_x(0, pin0);
+    if (t.nchunks > 1) {
+        fetch_w(1, pw1);
+        fetch_x(1, pin1);
+    }
     GSPC_STAMP(2)
 
     // ---- per-lane pixel coordinates ----------------------------------------
@@ -178,18 +183,14 @@ __global__ __launch_bounds__(64 * WM * WP) void conv_mfma16(ConvParams p, Tile16
         }
     }
     GSPC_STAMP(3)
-    commit(0);
+    commit(0, pin0, pw0);
     __syncthreads();
     GSPC_STAMP(4)
 
     // Software pipeline: iteration ch multiplies chunk ch out of LDS buffer
-    // ch&1 while chunk ch+1 travels global -> registers -> the other buffer.
-    for (int ch = 0; ch < t.nchunks; ++ch) {
-        const bool more = ch + 1 < t.nchunks;
-        if (more) {
-            fetch_w(ch + 1);
-            fetch_x(ch + 1);
-        }
+    // ch&1; chunk ch+1 moves registers -> the other LDS buffer at its end, and
+    // chunk ch+2 is requested from global memory at its start.
+    auto compute = [&](int ch) __attribute__((always_inline)) {
         const float *xs = smem + (ch & 1) * buf_floats;
         const float *ws = xs + t.in_floats + (wm * MI) * 64 + lane;
         for (int cb = 0; cb < t.CK / 4; ++cb) {
@@ -212,9 +213,27 @@ __global__ __launch_bounds__(64 * WM * WP) void conv_mfma16(ConvParams p, Tile16
                 }
             }
         }
-        if (more) {
-            commit((ch + 1) & 1);
+    };
+    for (int ch = 0; ch < t.nchunks; ch += 2) {
+        // even chunk: set 0 is free (chunk ch is in LDS), set 1 holds chunk ch+1
+        if (ch + 2 < t.nchunks) {
+            fetch_w(ch + 2, pw0);
+            fetch_x(ch + 2, pin0);
+        }
+        compute(ch);
+        if (ch + 1 < t.nchunks) {
+            commit((ch + 1) & 1, pin1, pw1);
             __syncthreads();
+            // odd chunk: set 1 is free, set 0 holds chunk ch+2
+            if (ch + 3 < t.nchunks) {
+                fetch_w(ch + 3, pw1);
+                fetch_x(ch + 3, pin1);
+            }
+            compute(ch + 1);
+            if (ch + 2 < t.nchunks) {
+                commit(ch & 1, pin0, pw0);
+                __syncthreads();
+            }
         }
     }
 

@@ -1,0 +1,68 @@
+"""Per-layer timing of gspc_conv2d_grouped-shaped work on the current stream.
+
+Each layer is replayed back to back inside one recorded layer chain (no host in
+the loop) and timed with events on the launch stream.  Returns rows with the
+Eq. 2 MAC count, the algorithmic bytes and the fractions of the nominal MI355X
+ceilings (fp32 MFMA 157.3 TFLOP/s, bf16 MFMA 2500 TFLOP/s, HBM 8 TB/s).
+"""
+import numpy as np
+
+from . import binding as b
+from . import workloads as wl
+
+PEAK_HBM_GBS = 8000.0
+PEAK_TFLOPS = {"f32": 157.3, "bf16": 2500.0}
+
+
+def layer_bytes(s, in_bytes):
+    ho, wo = wl.out_size(s.H, s.KH, s.stride, s.pad), wl.out_size(s.W, s.KW, s.stride, s.pad)
+    return (s.N * s.Cin * s.H * s.W * in_bytes + s.Cout * (s.Cin // s.groups) * s.KH * s.KW * 4
+            + s.N * s.Cout * ho * wo * 4)
+
+
+def time_layers(shapes, dtype="f32", inner=10, reps=10, rotate=1):
+    """shapes: list of workloads.ConvShape.  rotate > 1 cycles through that
+    many independent input/output buffer sets so that consecutive launches do
+    not find their data in cache (for HBM-bandwidth claims)."""
+    import torch
+    dev = torch.device("cuda:0")
+    b.gspc_set_stream()
+    rows = []
+    for s in shapes:
+        ho, wo = b.gspc_output_dims(s.H, s.W, s.KH, s.KW, s.stride, s.pad)
+        w = torch.randn((s.Cout, s.Cin // s.groups, s.KH, s.KW), device=dev) * 0.1
+        pw = b.gspc_pack_weights(w, s.groups, b.GSPC_BF16 if dtype == "bf16" else b.GSPC_F32)
+        n_in, n_out = s.N * s.Cin * s.H * s.W, s.N * s.Cout * ho * wo
+        bufs = []
+        for _ in range(rotate):
+            x = torch.rand(n_in, device=dev) * 2 - 1
+            if dtype == "bf16":
+                x = b.gspc_pack_input_bf16(x).view(torch.int16)
+            bufs += [x, torch.empty(n_out, dtype=torch.float32, device=dev)]
+        layers = []
+        for i in range(inner):
+            r = i % rotate
+            layers.append(wl.Layer("conv", 2 * r, -1, 2 * r + 1, s.N, s.Cin, s.H, s.W, s.Cout, s.KH,
+                                   s.KW, s.stride, s.pad, s.groups, False, 0))
+        lc = b.LayerChain(layers, [pw], bufs)
+        b.gspc_run_layer_chain(lc)
+        name = b.gspc_last_kernel()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(reps):
+            b.gspc_run_layer_chain(lc)
+        e1.record()
+        torch.cuda.synchronize()
+        us = e0.elapsed_time(e1) / (reps * inner) * 1e3
+        macs = wl.conv_macs(s)
+        nbytes = layer_bytes(s, 2 if dtype == "bf16" else 4)
+        rows.append({
+            "layer": f"{s.Cin}->{s.Cout} {s.H}x{s.W} k{s.KH} s{s.stride} g{s.groups} N{s.N}",
+            "kernel": name, "us": round(us, 2), "gmacs": round(macs / us / 1e3, 1),
+            "tflops": round(2 * macs / us / 1e6, 2), "gbs": round(nbytes / us / 1e3, 1),
+            "frac_mfma": round(2 * macs / us / 1e6 / PEAK_TFLOPS[dtype], 4),
+            "frac_hbm": round(nbytes / us / 1e3 / PEAK_HBM_GBS, 4),
+        })
+        del bufs, lc
+    return rows
