@@ -191,6 +191,105 @@ __global__ __launch_bounds__(256) void conv_direct_small(ConvParams p, TileS t) 
     }
 }
 
+// ---------------------------------------------------------------------------
+// Flat 3x3 kernel for the shapes the strip kernel cannot take (planes whose
+// width is not a multiple of 4, e.g. 14x14 and 7x7 depthwise layers): one thread
+// per output pixel of one (image, group), all KPG <= 4 filters of the group,
+// planes treated as flat memory so that neighbouring lanes read neighbouring
+// addresses even when a row is only 7 elements long.
+// ---------------------------------------------------------------------------
+struct TileF {
+    unsigned total;
+    float r_hwo;             // 1 / (Hout*Wout), for the one division whose numerator is large
+    unsigned m_wout, m_g;
+    unsigned x_bytes, w_bytes, y_bytes;
+};
+
+template <int KPG, typename TIN>
+__global__ __launch_bounds__(256) void conv_direct_flat(ConvParams p, TileF t) {
+    constexpr int ES = (int)sizeof(TIN);
+    const unsigned gt = blockIdx.x * 256 + threadIdx.x;
+    const bool live = gt < t.total;
+    const unsigned g0 = live ? gt : 0;
+    const unsigned HWo = p.Hout * p.Wout;
+    // g0 / HWo by reciprocal estimate and correction (g0 may be close to 2^32)
+    unsigned plane = (unsigned)(__uint2float_rz(g0) * t.r_hwo);
+    int rem = (int)(g0 - plane * HWo);
+    while (rem < 0) { --plane; rem += (int)HWo; }
+    while (rem >= (int)HWo) { ++plane; rem -= (int)HWo; }
+    const unsigned pix = (unsigned)rem;
+    const unsigned oh = fast_div(pix, t.m_wout), ow = pix - oh * p.Wout;
+    const unsigned n = fast_div(plane, t.m_g), j = plane - n * p.groups;
+    const int ih0 = (int)(oh * p.stride) - p.pad, iw0 = (int)(ow * p.stride) - p.pad;
+    const __amdgpu_buffer_rsrc_t rx = make_rsrc(p.x, t.x_bytes);
+    const __amdgpu_buffer_rsrc_t rw = make_rsrc(p.wd, t.w_bytes);
+    f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int c = 0; c < p.CPG; ++c) {
+        const unsigned cbase = ((n * p.Cin + j * p.CPG + c) * p.H) * p.W;
+        const unsigned wbase = ((j * p.CPG + c) * 9) * (p.KPGd * 4);
+#pragma unroll
+        for (int kh = 0; kh < 3; ++kh) {
+#pragma unroll
+            for (int kw = 0; kw < 3; ++kw) {
+                const int ih = ih0 + kh, iw = iw0 + kw;
+                const bool ok = live && ih >= 0 && ih < p.H && iw >= 0 && iw < p.W;
+                const float xv = buf_load_in<TIN>(rx, ok ? (cbase + ih * p.W + iw) * ES : kOob, 0, 0).x;
+                const f32x4 wk = __builtin_bit_cast(
+                    f32x4, __builtin_amdgcn_raw_buffer_load_b128(rw, wbase + (kh * 3 + kw) * (p.KPGd * 4), 0, 0));
+                acc += xv * wk;
+            }
+        }
+    }
+    const __amdgpu_buffer_rsrc_t ry = make_rsrc(p.y, t.y_bytes);
+    const __amdgpu_buffer_rsrc_t rr = make_rsrc(p.res ? p.res : p.y, p.res ? t.y_bytes : 0u);
+#pragma unroll
+    for (int o = 0; o < KPG; ++o) {
+        const unsigned off = live ? ((n * p.Cout + j * KPG + o) * HWo + pix) * 4 : kOob;
+        float v = acc[o];
+        if (p.res) v += __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rr, off, 0, 0));
+        if (p.relu) v = fmaxf(v, 0.f);
+        __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(v), ry, off, 0, 0);
+    }
+}
+
+namespace {
+
+bool plan_flat(const ConvParams &p, TileF *out) {
+    if (p.KH != 3 || p.KW != 3 || p.KPG > 4 || p.CPG > 8) return false;
+    const double total = (double)p.N * p.groups * p.Hout * p.Wout;
+    const double xb = (double)p.N * p.Cin * p.H * p.W * (p.in_bf16 ? 2 : 4);
+    const double yb = (double)p.N * p.Cout * p.Hout * p.Wout * 4;
+    const double wb = (double)p.groups * p.CPG * 9 * p.KPGd * 4;
+    if (total >= 4.0e9 || xb >= (double)kOob || yb >= (double)kOob || wb >= (double)kOob) return false;
+    const double hwo = (double)p.Hout * p.Wout;
+    // fast_div exactness: numerator * divisor < 2^32 at each step
+    if (hwo >= 1.0e6 || hwo * p.Wout >= 4.29e9 || (total / hwo) * p.groups >= 4.29e9) return false;
+    TileF t{};
+    t.total = (unsigned)total;
+    t.r_hwo = 1.0f / (float)(p.Hout * p.Wout);
+    t.m_wout = div_magic(p.Wout);
+    t.m_g = div_magic(p.groups);
+    t.x_bytes = (unsigned)xb;
+    t.y_bytes = (unsigned)yb;
+    t.w_bytes = (unsigned)wb;
+    *out = t;
+    return true;
+}
+
+template <typename TIN>
+hipError_t launch_flat(const ConvParams &p, const TileF &t, hipStream_t s) {
+    dim3 grid((t.total + 255) / 256);
+    switch (p.KPG) {
+    case 1: hipLaunchKernelGGL((conv_direct_flat<1, TIN>), grid, dim3(256), 0, s, p, t); break;
+    case 2: hipLaunchKernelGGL((conv_direct_flat<2, TIN>), grid, dim3(256), 0, s, p, t); break;
+    case 3: hipLaunchKernelGGL((conv_direct_flat<3, TIN>), grid, dim3(256), 0, s, p, t); break;
+    default: hipLaunchKernelGGL((conv_direct_flat<4, TIN>), grid, dim3(256), 0, s, p, t); break;
+    }
+    return hipGetLastError();
+}
+
+}  // namespace
+
 namespace {
 
 bool plan_small(const ConvParams &p, TileS *out) {
@@ -251,6 +350,11 @@ hipError_t launch_direct(const ConvParams &p, hipStream_t s, const char **name) 
                             std::to_string(p.stride) + "," + std::to_string(p.stride == 1 ? 4 : 2) +
                             (p.in_bf16 ? ",bf16>" : ",f32>"));
         return p.in_bf16 ? launch_small<uint16_t>(p, ts, s) : launch_small<float>(p, ts, s);
+    }
+    TileF tf;
+    if (plan_flat(p, &tf)) {
+        *name = intern_name("conv_direct_flat<" + std::to_string(p.KPG) + (p.in_bf16 ? ",bf16>" : ",f32>"));
+        return p.in_bf16 ? launch_flat<uint16_t>(p, tf, s) : launch_flat<float>(p, tf, s);
     }
     const bool oct8 = p.KPGd % 8 == 0;
     if (p.in_bf16) {

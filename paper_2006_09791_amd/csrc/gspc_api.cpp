@@ -122,6 +122,7 @@ int prepare_conv(const void *input, const gspc_packed_t *pw, int N, int Cin, int
                 ? reinterpret_cast<const float *>(static_cast<const char *>(pw->dev) +
                                                   pw->geom.mfma_offset)
                 : nullptr;
+    p->wb = pw->geom.bf16_bytes ? static_cast<const char *>(pw->dev) + pw->geom.bf16_offset : nullptr;
     p->y = static_cast<float *>(output);
     p->res = nullptr;
     p->N = N; p->Cin = Cin; p->H = H; p->W = W; p->Cout = Cout; p->KH = KH; p->KW = KW;
@@ -153,7 +154,7 @@ int dispatch_conv(const gspc::ConvParams &p, const gspc_packed_t *pw) {
 
 namespace gspc {
 
-PackGeom make_pack_geom(int Cin, int Cout, int KH, int KW, int groups, int /*dtype*/) {
+PackGeom make_pack_geom(int Cin, int Cout, int KH, int KW, int groups, int dtype) {
     PackGeom g{};
     g.CPG = Cin / groups;
     g.KPG = Cout / groups;
@@ -171,7 +172,14 @@ PackGeom make_pack_geom(int Cin, int Cout, int KH, int KW, int groups, int /*dty
         g.mfma_bytes = (size_t)groups * g.mtiles * g.ksteps * 64 * sizeof(float);
     }
     g.mfma_offset = (g.direct_bytes + 255) / 256 * 256;
-    g.total_bytes = g.mfma_offset + g.mfma_bytes;
+    g.bf16_offset = (g.mfma_offset + g.mfma_bytes + 255) / 256 * 256;
+    if (dtype == GSPC_BF16 && KH == 3 && KW == 3 && g.KPG % 16 == 0 && g.CPG % 8 == 0) {
+        g.ckb = g.CPG % 32 == 0 ? 32 : g.CPG % 16 == 0 ? 16 : 8;
+        g.nchunks_b = g.CPG / g.ckb;
+        g.ks_b = (9 * g.ckb / 8 + 3) / 4;
+        g.bf16_bytes = (size_t)groups * g.nchunks_b * g.ks_b * (g.KPG / 16) * 1024;
+    }
+    g.total_bytes = g.bf16_bytes ? g.bf16_offset + g.bf16_bytes : g.mfma_offset + g.mfma_bytes;
     return g;
 }
 

@@ -37,6 +37,14 @@ struct PackGeom {
     int variant;   // MfmaVariant
     int ksub, CPGp, ksteps, mtiles;
     size_t direct_bytes, mfma_bytes, mfma_offset, total_bytes;
+    // bf16 matrix-core section (GSPC_BF16 handles, 3x3, KPG % 16 == 0, CPG % 8 == 0):
+    // bf16 [g][chunk][k-step][KPG/16][64 lanes][8], the A operand of one
+    // v_mfma_f32_16x16x32_bf16 per (chunk, k-step, filter tile, lane).  A chunk
+    // covers ckb input channels; its reduction is cut into units of 8 channels
+    // at one tap, unit u = tap*(ckb/8) + channel block; lane l of k-step s holds
+    // unit 4*s + l/16 of filter l%16 (zeros past the last unit).
+    int ckb, ks_b, nchunks_b;
+    size_t bf16_bytes, bf16_offset;
 };
 
 PackGeom make_pack_geom(int Cin, int Cout, int KH, int KW, int groups, int dtype);
@@ -59,6 +67,7 @@ struct ConvParams {
     const void *x;      // [N][Cin][H][W], fp32 or bf16
     const float *wd;    // direct section
     const float *wm;    // mfma section (nullptr if none)
+    const void *wb;     // bf16 mfma section (nullptr if none)
     float *y;           // [N][Cout][Hout][Wout]
     const float *res;   // optional residual, same shape as y
     int N, Cin, H, W, Cout, KH, KW, stride, pad, groups;
@@ -74,6 +83,15 @@ hipError_t launch_direct(const ConvParams &p, hipStream_t s, const char **name);
 hipError_t launch_mfma(const ConvParams &p, const PackGeom &g, hipStream_t s,
                        const char **name);
 bool mfma_supported(const ConvParams &p, const PackGeom &g);
+
+// bf16 16x16x32 MFMA kernel; plan is opaque to the caller.
+struct MfmaB16Plan {
+    int inst;
+    int data[48];
+};
+bool plan_mfma_bf16(const ConvParams &p, const PackGeom &g, MfmaB16Plan *out);
+hipError_t launch_mfma_bf16(const ConvParams &p, const PackGeom &g, const MfmaB16Plan &plan, hipStream_t s,
+                            const char **name);
 
 // 4x4x1 MFMA kernel (weights held in registers); plan is opaque to the caller.
 struct Mfma4Plan {

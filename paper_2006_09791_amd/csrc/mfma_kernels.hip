@@ -496,16 +496,18 @@ struct Plan {
     int idx;
     Tile16 t16;
     Mfma4Plan p4;
+    MfmaB16Plan pb;
 };
 
 const Plan &get_plan(const ConvParams &p, const PackGeom &g) {
     thread_local std::unordered_map<PlanKey, Plan, PlanKeyHash> cache;
     PlanKey k{{p.N, p.Cin, p.H, p.W, p.Cout, p.KH, p.KW, p.stride, p.pad, p.groups, p.in_bf16,
-               g.variant, p.wm != nullptr, 0}};
+               g.variant, p.wm != nullptr, p.wb != nullptr}};
     auto it = cache.find(k);
     if (it != cache.end()) return it->second;
     Plan pl{};
-    if (plan16(p, g, &pl.idx, &pl.t16)) pl.kind = 16;
+    if (plan_mfma_bf16(p, g, &pl.pb)) pl.kind = 32;
+    else if (plan16(p, g, &pl.idx, &pl.t16)) pl.kind = 16;
     else if (plan_mfma4(p, g, &pl.p4)) pl.kind = 4;
     return cache.emplace(k, pl).first->second;
 }
@@ -524,6 +526,7 @@ hipError_t launch_mfma(const ConvParams &p, const PackGeom &g, hipStream_t s, co
                             (p.in_bf16 ? ",bf16>" : ",f32>"));
         return p.in_bf16 ? launch16_cfg<uint16_t>(pl.idx, p, pl.t16, s) : launch16_cfg<float>(pl.idx, p, pl.t16, s);
     }
+    if (pl.kind == 32) return launch_mfma_bf16(p, g, pl.pb, s, name);
     if (pl.kind == 4) return launch_mfma4(p, pl.p4, s, name);
     return hipErrorNotSupported;
 }

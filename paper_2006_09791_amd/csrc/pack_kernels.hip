@@ -62,6 +62,33 @@ __global__ void pack_mfma_kernel(const float *__restrict__ w, float *__restrict_
     out[d] = v;
 }
 
+// bf16 matrix-core section, one thread per 2-byte element.
+__global__ void pack_bf16_kernel(const float *__restrict__ w, uint16_t *__restrict__ out, PackArgs a,
+                                 int ckb, int ks_b, int nchunks, size_t total) {
+    size_t d = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (d >= total) return;
+    const int e = (int)(d % 8);
+    size_t r = d / 8;
+    const int lane = (int)(r % 64);
+    r /= 64;
+    const int mtiles = a.KPG / 16;
+    const int mt = (int)(r % mtiles);
+    r /= mtiles;
+    const int ks = (int)(r % ks_b);
+    r /= ks_b;
+    const int chunk = (int)(r % nchunks);
+    const int j = (int)(r / nchunks);
+    const int u8 = ckb / 8, u = 4 * ks + lane / 16;
+    uint16_t v = 0;
+    if (u < 9 * u8) {
+        const int tap = u / u8, cb8 = u % u8;
+        const int c = chunk * ckb + cb8 * 8 + e;
+        const int oc = j * a.KPG + mt * 16 + lane % 16;
+        v = (uint16_t)(__float_as_uint(round_bf16(w[(size_t)oc * a.Kred + (size_t)c * 9 + tap])) >> 16);
+    }
+    out[d] = v;
+}
+
 __global__ void unpack_kernel(const float *__restrict__ sec, float *__restrict__ w, PackArgs a,
                               int from_mfma, size_t total) {
     size_t d = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -112,6 +139,14 @@ hipError_t launch_pack_weights(const float *w, const gspc_packed *h, hipStream_t
                        nd, nd_gap);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
+    if (h->geom.bf16_bytes) {
+        uint16_t *bsec = reinterpret_cast<uint16_t *>(static_cast<char *>(h->dev) + h->geom.bf16_offset);
+        const size_t nb = h->geom.bf16_bytes / 2;
+        hipLaunchKernelGGL(pack_bf16_kernel, dim3(blocks_for(nb, 256)), dim3(256), 0, s, w, bsec, a,
+                           h->geom.ckb, h->geom.ks_b, h->geom.nchunks_b, nb);
+        e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
     if (h->geom.mfma_bytes) {
         float *msec = reinterpret_cast<float *>(static_cast<char *>(h->dev) + h->geom.mfma_offset);
         const size_t nm = h->geom.mfma_bytes / sizeof(float);

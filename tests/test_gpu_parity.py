@@ -161,6 +161,11 @@ def test_bf16_cast_matches_host_rounding(gpu):
     S(2, 64, 14, 14, 64, 3, 3, 1, 1, 2),
     S(2, 64, 14, 14, 128, 3, 3, 2, 1, 8),
     S(1, 64, 12, 12, 64, 3, 3, 1, 1, 32),
+    S(2, 128, 7, 7, 128, 3, 3, 1, 1, 2),      # two chunks of 32 channels, odd width (2-byte loads)
+    S(1, 64, 56, 56, 64, 3, 3, 1, 1, 2),      # row blocks with a ragged tail, 8-byte loads
+    S(3, 32, 9, 12, 64, 3, 3, 2, 1, 2),       # 16 channels per group, stride 2, odd height
+    S(2, 48, 10, 10, 32, 3, 3, 1, 1, 2),      # 24 channels per group: chunks of 8
+    S(1, 256, 8, 8, 512, 3, 3, 2, 1, 2),      # four chunks, 256 filters per group
 ], ids=lambda s: "x".join(map(str, s)))
 def test_bf16_layers(gpu, s):
     torch, b = gpu
