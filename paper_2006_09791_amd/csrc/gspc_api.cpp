@@ -173,11 +173,12 @@ PackGeom make_pack_geom(int Cin, int Cout, int KH, int KW, int groups, int dtype
     }
     g.mfma_offset = (g.direct_bytes + 255) / 256 * 256;
     g.bf16_offset = (g.mfma_offset + g.mfma_bytes + 255) / 256 * 256;
-    if (dtype == GSPC_BF16 && KH == 3 && KW == 3 && g.KPG % 16 == 0 && g.CPG % 8 == 0) {
+    if (dtype == GSPC_BF16 && KH == 3 && KW == 3 && g.KPG % 4 == 0 && g.CPG % 8 == 0) {
         g.ckb = g.CPG % 32 == 0 ? 32 : g.CPG % 16 == 0 ? 16 : 8;
         g.nchunks_b = g.CPG / g.ckb;
         g.ks_b = (9 * g.ckb / 8 + 3) / 4;
-        g.bf16_bytes = (size_t)groups * g.nchunks_b * g.ks_b * (g.KPG / 16) * 1024;
+        g.mtiles_b = (g.KPG + 15) / 16;   // filter tiles, the last one zero-padded
+        g.bf16_bytes = (size_t)groups * g.nchunks_b * g.ks_b * g.mtiles_b * 1024;
     }
     g.total_bytes = g.bf16_bytes ? g.bf16_offset + g.bf16_bytes : g.mfma_offset + g.mfma_bytes;
     return g;

@@ -37,13 +37,13 @@ struct PackGeom {
     int variant;   // MfmaVariant
     int ksub, CPGp, ksteps, mtiles;
     size_t direct_bytes, mfma_bytes, mfma_offset, total_bytes;
-    // bf16 matrix-core section (GSPC_BF16 handles, 3x3, KPG % 16 == 0, CPG % 8 == 0):
-    // bf16 [g][chunk][k-step][KPG/16][64 lanes][8], the A operand of one
+    // bf16 matrix-core section (GSPC_BF16 handles, 3x3, KPG % 4 == 0, CPG % 8 == 0):
+    // bf16 [g][chunk][k-step][ceil(KPG/16)][64 lanes][8], the A operand of one
     // v_mfma_f32_16x16x32_bf16 per (chunk, k-step, filter tile, lane).  A chunk
     // covers ckb input channels; its reduction is cut into units of 8 channels
     // at one tap, unit u = tap*(ckb/8) + channel block; lane l of k-step s holds
     // unit 4*s + l/16 of filter l%16 (zeros past the last unit).
-    int ckb, ks_b, nchunks_b;
+    int ckb, ks_b, nchunks_b, mtiles_b;
     size_t bf16_bytes, bf16_offset;
 };
 

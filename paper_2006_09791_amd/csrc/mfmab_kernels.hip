@@ -1,6 +1,7 @@
 // bf16 grouped 3x3 convolution on v_mfma_f32_16x16x32_bf16 (fp32 accumulate,
 // fp32 NCHW output): the per-group implicit GEMM of mfma_kernels.hip with bf16
-// operands, for GSPC_BF16 layers with KPG % 16 == 0 and CPG % 8 == 0.
+// operands, for GSPC_BF16 layers with KPG % 4 == 0 and CPG % 8 == 0 (the last
+// 16-filter tile of a group is zero-padded and its surplus rows are not stored).
 //
 // Operand layout of the instruction (lane l of 64): A = filter row l%16,
 // reduction slots 8*(l/16) .. 8*(l/16)+7; B = the same slots of pixel column
@@ -198,8 +199,9 @@ __global__ __launch_bounds__(64 * WM * WP) void conv_mfma16b(ConvParams p, TileB
             for (int ni = 0; ni < NI; ++ni)
 #pragma unroll
                 for (int r = 0; r < 4; ++r)
-                    acc[mi][ni][r] += __uint_as_float(
-                        __builtin_amdgcn_raw_buffer_load_b32(rr, ooff[ni], (oc0 + mi * 16 + r) * HWo * 4, 0));
+                    acc[mi][ni][r] += __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(
+                        rr, oc0 + mi * 16 + 4 * (lane >> 4) < (unsigned)p.KPG ? ooff[ni] : kOob,
+                        (oc0 + mi * 16 + r) * HWo * 4, 0));
     }
 #pragma unroll
     for (int mi = 0; mi < MI; ++mi)
@@ -209,8 +211,10 @@ __global__ __launch_bounds__(64 * WM * WP) void conv_mfma16b(ConvParams p, TileB
             for (int r = 0; r < 4; ++r) {
                 float v = acc[mi][ni][r];
                 if (p.relu) v = fmaxf(v, 0.f);
-                __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(v), ry, ooff[ni],
-                                                      (oc0 + mi * 16 + r) * HWo * 4, 0);
+                // rows past KPG belong to the zero-padded part of the last filter tile
+                __builtin_amdgcn_raw_buffer_store_b32(
+                    __float_as_uint(v), ry, oc0 + mi * 16 + 4 * (lane >> 4) < (unsigned)p.KPG ? ooff[ni] : kOob,
+                    (oc0 + mi * 16 + r) * HWo * 4, 0);
             }
 }
 
@@ -219,17 +223,17 @@ __global__ __launch_bounds__(64 * WM * WP) void conv_mfma16b(ConvParams p, TileB
 // ---------------------------------------------------------------------------
 namespace {
 
-constexpr int kLdsBudgetB = 48 * 1024;
+constexpr int kLdsBudgetB = 64 * 1024;
 
 struct CfgB {
     int MI, NI, WM, WP;
 };
-const CfgB kCfgB[] = {{2, 4, 1, 4}, {1, 4, 1, 4}, {2, 2, 1, 4}, {1, 2, 1, 4}};
+const CfgB kCfgB[] = {{2, 4, 1, 4}, {1, 4, 1, 4}, {2, 2, 1, 4}, {1, 2, 1, 4}, {2, 1, 1, 4}, {1, 1, 1, 4}};
 constexpr int kNumCfgB = sizeof(kCfgB) / sizeof(kCfgB[0]);
 
 bool planB_cfg(const ConvParams &p, const PackGeom &g, const CfgB &c, TileB *out) {
     const int MB = 16 * c.MI * c.WM, PB = 16 * c.NI * c.WP, NT = 64 * c.WM * c.WP;
-    if (g.KPG % MB) return false;
+    if ((g.mtiles_b * 16) % MB) return false;
     TileB t{};
     if (!split_pixels(p, PB, &t.NB, &t.TH)) return false;
     t.IHt = (t.TH - 1) * p.stride + 3;
@@ -246,10 +250,10 @@ bool planB_cfg(const ConvParams &p, const PackGeom &g, const CfgB &c, TileB *out
     const size_t lds = (size_t)t.in_bytes + (size_t)t.wslots * NT * 16;
     if (lds > (size_t)kLdsBudgetB) return false;
     t.nchunks = g.nchunks_b;
-    t.mtiles = g.KPG / 16;
+    t.mtiles = g.mtiles_b;
     t.row_blocks = (p.Hout + t.TH - 1) / t.TH;
     t.img_blocks = (p.N + t.NB - 1) / t.NB;
-    t.oc_blocks = g.KPG / MB;
+    t.oc_blocks = g.mtiles_b * 16 / MB;
     t.m_CG = div_magic(t.CG);
     t.m_IHt = div_magic(t.IHt);
     t.m_NB = div_magic(t.NB);
@@ -344,6 +348,8 @@ hipError_t launch_mfma_bf16(const ConvParams &p, const PackGeom &g, const MfmaB1
     case 1: return launchB_s<1, 4, 1, 4>(g.ckb, vw, p, t, s);
     case 2: return launchB_s<2, 2, 1, 4>(g.ckb, vw, p, t, s);
     case 3: return launchB_s<1, 2, 1, 4>(g.ckb, vw, p, t, s);
+    case 4: return launchB_s<2, 1, 1, 4>(g.ckb, vw, p, t, s);
+    case 5: return launchB_s<1, 1, 1, 4>(g.ckb, vw, p, t, s);
     }
     return hipErrorNotSupported;
 }

@@ -71,7 +71,7 @@ __global__ void pack_bf16_kernel(const float *__restrict__ w, uint16_t *__restri
     size_t r = d / 8;
     const int lane = (int)(r % 64);
     r /= 64;
-    const int mtiles = a.KPG / 16;
+    const int mtiles = (a.KPG + 15) / 16;
     const int mt = (int)(r % mtiles);
     r /= mtiles;
     const int ks = (int)(r % ks_b);
@@ -80,7 +80,7 @@ __global__ void pack_bf16_kernel(const float *__restrict__ w, uint16_t *__restri
     const int j = (int)(r / nchunks);
     const int u8 = ckb / 8, u = 4 * ks + lane / 16;
     uint16_t v = 0;
-    if (u < 9 * u8) {
+    if (u < 9 * u8 && mt * 16 + lane % 16 < a.KPG) {
         const int tap = u / u8, cb8 = u % u8;
         const int c = chunk * ckb + cb8 * 8 + e;
         const int oc = j * a.KPG + mt * 16 + lane % 16;

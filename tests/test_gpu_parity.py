@@ -166,6 +166,8 @@ def test_bf16_cast_matches_host_rounding(gpu):
     S(3, 32, 9, 12, 64, 3, 3, 2, 1, 2),       # 16 channels per group, stride 2, odd height
     S(2, 48, 10, 10, 32, 3, 3, 1, 1, 2),      # 24 channels per group: chunks of 8
     S(1, 256, 8, 8, 512, 3, 3, 2, 1, 2),      # four chunks, 256 filters per group
+    S(2, 64, 14, 14, 64, 3, 3, 1, 1, 8),      # 8 filters per group: half of the filter tile is padding
+    S(1, 48, 10, 10, 144, 3, 3, 1, 1, 6),     # 24 filters per group: ragged last filter tile
 ], ids=lambda s: "x".join(map(str, s)))
 def test_bf16_layers(gpu, s):
     torch, b = gpu
