@@ -52,7 +52,7 @@ def main():
     ap.add_argument("--traffic-probe", action="store_true",
                     help="first run a plain 256 MiB device copy three times: the known-size kernel "
                          "against which rocprofv3's FETCH_SIZE / WRITE_SIZE counters are scaled")
-    ap.add_argument("--sweep", choices=["wrn", "resnet_bf16", "depthwise"],
+    ap.add_argument("--sweep", choices=["wrn", "resnet_bf16", "depthwise", "latency"],
                     help="instead of the headline step, time every layer of a configuration family "
                          "and print one JSON line with a row per layer")
     ap.add_argument("--serial", action="store_true",
@@ -85,6 +85,31 @@ def main():
         if args.sweep == "wrn":
             shapes = [s for g in GROUPS for s in wl.wrn_grouped_shapes(BATCH, g)]
             rows = layer_timing.time_layers(shapes, "f32")
+        elif args.sweep == "latency":
+            # whole-network latency at batch 1 (recorded chains replayed back to back)
+            rows = []
+            nets = [(f"wrn40x2-style g={g}", wl.wrn_chain(1, g), 2) for g in GROUPS]
+            nets += [(f"resnet34-shaped g={g}", wl.resnet34_chain(1, g), 3) for g in (2, 4, 8, 16, 32)]
+            nets += [(f"depthwise+pointwise C={C} {hw}x{hw} s{st}", wl.mobilenet_dw_chain(1, C, hw, st), 4)
+                     for C, hw in wl.DEPTHWISE_CH_HW for st in (1, 2)]
+            for name, ch, cfg in nets:
+                weights = ch.make_weights(cfg)
+                packed = [b.gspc_pack_weights(torch.from_numpy(w).to(dev), gg)
+                          for w, gg in zip(weights, ch.weight_groups)]
+                bufs = [torch.empty(max(n, 1), dtype=torch.float32, device=dev) for n in ch.buf_elems]
+                bufs[0].copy_(torch.from_numpy(wl.make_input(ch.input_shape, 1)).reshape(-1))
+                lc = b.LayerChain(ch.layers, packed, bufs)
+                for _ in range(5):
+                    b.gspc_run_layer_chain(lc)
+                torch.cuda.synchronize()
+                reps = 100
+                ta = time.perf_counter()
+                for _ in range(reps):
+                    b.gspc_run_layer_chain(lc)
+                torch.cuda.synchronize()
+                ms = (time.perf_counter() - ta) / reps * 1e3
+                rows.append({"network": name, "layers": len(ch.layers), "mmacs": round(ch.macs() / 1e6, 2),
+                             "latency_ms": round(ms, 4), "gmacs": round(ch.macs() / ms / 1e6, 1)})
         elif args.sweep == "resnet_bf16":
             shapes = [s for g in (2, 8, 32) for s in wl.resnet34_grouped_shapes(256, g)]
             rows = layer_timing.time_layers(shapes, "bf16", inner=4, reps=5)
