@@ -41,6 +41,7 @@ struct Tile16 {
     int xslots, wslots;      // staged rows / weight float4 per thread per chunk
     int ksteps, mtiles;      // geometry of the packed weight section
     int in_floats, w_floats; // per LDS buffer (a buffer is in | w | 4 spare floats)
+    int ksplit;              // 1: the four waves share one pixel tile and split the reduction
     unsigned m_IHt, m_NB, m_ppi, m_Wout, m_rowb, m_ocb;  // multiply-high reciprocals (0 = divisor 1)
     unsigned x_bytes, w_bytes, y_bytes;                  // extents for the buffer descriptors
 };
@@ -68,7 +69,12 @@ __global__ __launch_bounds__(64 * WM * WP) void conv_mfma16(ConvParams p, Tile16
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wm = wave / WP, wp = wave % WP;
+    // Normally the WP pixel-side waves own different pixel runs.  With ksplit they
+    // all own the same runs and take every fourth 4-channel block of the
+    // reduction instead (small batches: more, shorter blocks), and their partial
+    // sums are added through LDS at the end.
+    const int wm = wave / WP, wp = t.ksplit ? 0 : wave % WP;
+    const int wk = t.ksplit ? wave : 0, kstride = t.ksplit ? WM * WP : 1;
     const unsigned ib = fast_div(blockIdx.x, t.m_rowb);
     const int rb = blockIdx.x - ib * t.row_blocks;
     const unsigned j = fast_div(blockIdx.y, t.m_ocb);
@@ -193,7 +199,7 @@ __global__ __launch_bounds__(64 * WM * WP) void conv_mfma16(ConvParams p, Tile16
     auto compute = [&](int ch) __attribute__((always_inline)) {
         const float *xs = smem + (ch & 1) * buf_floats;
         const float *ws = xs + t.in_floats + (wm * MI) * 64 + lane;
-        for (int cb = 0; cb < t.CK / 4; ++cb) {
+        for (int cb = wk; cb < t.CK / 4; cb += kstride) {
             const float *xrow = xs + cb * 4 * t.PLANE;
             const float *wrw = ws + cb * TAPS * MIWM * 64;
 #pragma unroll
@@ -238,6 +244,22 @@ __global__ __launch_bounds__(64 * WM * WP) void conv_mfma16(ConvParams p, Tile16
     }
 
     GSPC_STAMP(5)
+    if (t.ksplit) {
+        __syncthreads();   // staging buffers are free: reuse them for the partial sums
+        if (wave != 0) {
+#pragma unroll
+            for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+                for (int ni = 0; ni < NI; ++ni) smem4[((wave * MI + mi) * NI + ni) * 64 + lane] = acc[mi][ni];
+        }
+        __syncthreads();
+        if (wave != 0) return;
+        for (int w = 1; w < WM * WP; ++w)
+#pragma unroll
+            for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+                for (int ni = 0; ni < NI; ++ni) acc[mi][ni] += smem4[((w * MI + mi) * NI + ni) * 64 + lane];
+    }
     // ---- epilogue: optional residual and ReLU, NCHW store -------------------
     // Register r of tile (mi, ni) is filter 16*(tile row) + 4*(lane/16) + r at
     // this lane's pixel; the 4*(lane/16) part already sits in ooff.
@@ -283,19 +305,18 @@ constexpr int kLdsBudget16 = 40 * 1024;   // four blocks per CU out of 160 KB
 constexpr size_t kLdsMax = 160 * 1024;
 
 struct Cfg16 {
-    int MI, NI, WM, WP;
-    const char *name;
+    int MI, NI, WM, WP, ksplit;
 };
 
-// Instantiated block shapes (filters x pixels), largest first.
+// Instantiated block shapes, largest first; the ksplit entries reuse the WM = 1,
+// WP = 4 instances with all four waves on one 16*MI x 16*NI tile.
 const Cfg16 kCfg16[] = {
-    {4, 4, 1, 4, "conv_mfma16<64x256>"},  {2, 4, 1, 4, "conv_mfma16<32x256>"},
-    {4, 2, 1, 4, "conv_mfma16<64x128>"},  {2, 2, 1, 4, "conv_mfma16<32x128>"},
-    {1, 4, 1, 4, "conv_mfma16<16x256>"},  {2, 2, 2, 2, "conv_mfma16<64x64>"},
-    {1, 2, 1, 4, "conv_mfma16<16x128>"},  {2, 1, 1, 4, "conv_mfma16<32x64>"},
-    {1, 1, 1, 4, "conv_mfma16<16x64>"},
+    {4, 4, 1, 4, 0}, {2, 4, 1, 4, 0}, {4, 2, 1, 4, 0}, {2, 2, 1, 4, 0}, {1, 4, 1, 4, 0}, {2, 2, 2, 2, 0},
+    {1, 2, 1, 4, 0}, {2, 1, 1, 4, 0}, {1, 1, 1, 4, 0},
+    {2, 2, 1, 4, 1}, {1, 2, 1, 4, 1}, {2, 1, 1, 4, 1}, {1, 1, 1, 4, 1},
 };
 constexpr int kNumCfg16 = sizeof(kCfg16) / sizeof(kCfg16[0]);
+constexpr int kFirstKsplit = 9;
 
 bool shape_instantiated(int KH, int KW, int S) {
     return (KH == 3 && KW == 3 && (S == 1 || S == 2)) || (KH == 1 && KW == 1 && (S == 1 || S == 2)) ||
@@ -322,9 +343,10 @@ int bank_cost(const ConvParams &p, const Tile16 &t, int plane) {
 }
 
 bool plan16_cfg(const ConvParams &p, const PackGeom &g, const Cfg16 &c, Tile16 *out) {
-    const int MB = 16 * c.MI * c.WM, PB = 16 * c.NI * c.WP, NT = 64 * c.WM * c.WP;
+    const int MB = 16 * c.MI * c.WM, PB = 16 * c.NI * (c.ksplit ? 1 : c.WP), NT = 64 * c.WM * c.WP;
     if (g.KPG % MB) return false;
     Tile16 t{};
+    t.ksplit = c.ksplit;
     if (!split_pixels(p, PB, &t.NB, &t.TH)) return false;
     t.IHt = (t.TH - 1) * p.stride + p.KH;
     t.vec = p.W % 4 == 0;
@@ -364,7 +386,7 @@ bool plan16_cfg(const ConvParams &p, const PackGeom &g, const Cfg16 &c, Tile16 *
         const int CK = 4 * d;
         const int wsl = (c.MI * c.WM * d * taps * 16 + NT - 1) / NT;
         const size_t in_f = (size_t)CK * t.PLANE, w_f = (size_t)wsl * NT * 4;
-        if (2 * (in_f + w_f + 4) * sizeof(float) > (size_t)kLdsBudget16) continue;
+        if (2 * (in_f + w_f + 4) * sizeof(float) > (size_t)(c.ksplit ? 2 * kLdsBudget16 : kLdsBudget16)) continue;
         if ((CK * t.NB * t.IHt + rpp - 1) / rpp > kTmax16) continue;
         if (wsl > kWmax16) continue;
         best = d;
@@ -413,7 +435,7 @@ bool plan16(const ConvParams &p, const PackGeom &g, int *cfg_idx, Tile16 *t_out)
     int best = -1;
     long best_blocks = -1;
     Tile16 bt{};
-    for (int i = 0; i < kNumCfg16; ++i) {
+    for (int i = 0; i < kFirstKsplit; ++i) {
         Tile16 t;
         if (!plan16_cfg(p, g, kCfg16[i], &t)) continue;
         const long blocks = (long)t.row_blocks * t.img_blocks * t.oc_blocks * p.groups;
@@ -428,6 +450,21 @@ bool plan16(const ConvParams &p, const PackGeom &g, int *cfg_idx, Tile16 *t_out)
             bt = t;
         }
     }
+    // Too few blocks to fill the GPU and a long reduction (small batches): let
+    // the waves of a block split the reduction instead of the pixels.
+    static const bool no_ksplit = std::getenv("GSPC_NO_KSPLIT") != nullptr;
+    if (!no_ksplit && best_blocks < 2 * kNumCU && g.ksteps >= 36) {
+        for (int i = kFirstKsplit; i < kNumCfg16; ++i) {
+            Tile16 t;
+            if (!plan16_cfg(p, g, kCfg16[i], &t)) continue;
+            const long blocks = (long)t.row_blocks * t.img_blocks * t.oc_blocks * p.groups;
+            if (blocks >= kNumCU || i == kNumCfg16 - 1) {
+                *cfg_idx = i;
+                *t_out = t;
+                return true;
+            }
+        }
+    }
     if (best < 0) return false;
     *cfg_idx = best;
     *t_out = bt;
@@ -436,7 +473,8 @@ bool plan16(const ConvParams &p, const PackGeom &g, int *cfg_idx, Tile16 *t_out)
 
 template <int MI, int NI, int WM, int WP, int KH, int KW, int S, typename TIN>
 hipError_t launch16_inst(const ConvParams &p, const Tile16 &t, hipStream_t s) {
-    const size_t lds = 2 * ((size_t)t.in_floats + t.w_floats + 4) * sizeof(float);
+    size_t lds = 2 * ((size_t)t.in_floats + t.w_floats + 4) * sizeof(float);
+    if (t.ksplit && lds < (size_t)WM * WP * MI * NI * 1024) lds = (size_t)WM * WP * MI * NI * 1024;
     dim3 grid(t.row_blocks * t.img_blocks, p.groups * t.oc_blocks);
     auto kern = conv_mfma16<MI, NI, WM, WP, KH, KW, S, TIN>;
     if (lds > 64 * 1024) {
@@ -474,6 +512,10 @@ hipError_t launch16_cfg(int i, const ConvParams &p, const Tile16 &t, hipStream_t
     case 6: return launch16_shape<1, 2, 1, 4, TIN>(p, t, s);
     case 7: return launch16_shape<2, 1, 1, 4, TIN>(p, t, s);
     case 8: return launch16_shape<1, 1, 1, 4, TIN>(p, t, s);
+    case 9: return launch16_shape<2, 2, 1, 4, TIN>(p, t, s);    // ksplit entries
+    case 10: return launch16_shape<1, 2, 1, 4, TIN>(p, t, s);
+    case 11: return launch16_shape<2, 1, 1, 4, TIN>(p, t, s);
+    case 12: return launch16_shape<1, 1, 1, 4, TIN>(p, t, s);
     }
     return hipErrorNotSupported;
 }
