@@ -342,7 +342,7 @@ int bank_cost(const ConvParams &p, const Tile16 &t, int plane) {
     return worst;
 }
 
-bool plan16_cfg(const ConvParams &p, const PackGeom &g, const Cfg16 &c, Tile16 *out) {
+bool plan16_cfg(const ConvParams &p, const PackGeom &g, const Cfg16 &c, Tile16 *out, int lds_budget = kLdsBudget16) {
     const int MB = 16 * c.MI * c.WM, PB = 16 * c.NI * (c.ksplit ? 1 : c.WP), NT = 64 * c.WM * c.WP;
     if (g.KPG % MB) return false;
     Tile16 t{};
@@ -386,7 +386,7 @@ bool plan16_cfg(const ConvParams &p, const PackGeom &g, const Cfg16 &c, Tile16 *
         const int CK = 4 * d;
         const int wsl = (c.MI * c.WM * d * taps * 16 + NT - 1) / NT;
         const size_t in_f = (size_t)CK * t.PLANE, w_f = (size_t)wsl * NT * 4;
-        if (2 * (in_f + w_f + 4) * sizeof(float) > (size_t)(c.ksplit ? 2 * kLdsBudget16 : kLdsBudget16)) continue;
+        if (2 * (in_f + w_f + 4) * sizeof(float) > (size_t)(c.ksplit ? 2 * lds_budget : lds_budget)) continue;
         if ((CK * t.NB * t.IHt + rpp - 1) / rpp > kTmax16) continue;
         if (wsl > kWmax16) continue;
         best = d;
@@ -465,7 +465,17 @@ bool plan16(const ConvParams &p, const PackGeom &g, int *cfg_idx, Tile16 *t_out)
             }
         }
     }
-    if (best < 0) return false;
+    if (best < 0) {
+        // Nothing fits the occupancy-friendly LDS budget (wide rows, 7x7 taps):
+        // take the first shape that fits in most of a CU's LDS.
+        for (int i = 0; i < kFirstKsplit; ++i) {
+            if (plan16_cfg(p, g, kCfg16[i], t_out, 144 * 1024)) {
+                *cfg_idx = i;
+                return true;
+            }
+        }
+        return false;
+    }
     *cfg_idx = best;
     *t_out = bt;
     return true;
@@ -565,7 +575,7 @@ hipError_t launch_mfma(const ConvParams &p, const PackGeom &g, hipStream_t s, co
         *name = intern_name("conv_mfma16<" + std::to_string(c.MI) + "," + std::to_string(c.NI) + "," +
                             std::to_string(c.WM) + "," + std::to_string(c.WP) + "," + std::to_string(p.KH) +
                             "," + std::to_string(p.KW) + "," + std::to_string(p.stride) +
-                            (p.in_bf16 ? ",bf16>" : ",f32>"));
+                            (p.in_bf16 ? ",bf16>" : ",f32>") + (c.ksplit ? "/ksplit" : ""));
         return p.in_bf16 ? launch16_cfg<uint16_t>(pl.idx, p, pl.t16, s) : launch16_cfg<float>(pl.idx, p, pl.t16, s);
     }
     if (pl.kind == 32) return launch_mfma_bf16(p, g, pl.pb, s, name);
