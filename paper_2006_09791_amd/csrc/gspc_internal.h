@@ -93,6 +93,14 @@ bool plan_mfma_bf16(const ConvParams &p, const PackGeom &g, MfmaB16Plan *out);
 hipError_t launch_mfma_bf16(const ConvParams &p, const PackGeom &g, const MfmaB16Plan &plan, hipStream_t s,
                             const char **name);
 
+// 16x16x4 MFMA kernel with the filter tile resident in LDS (3x3, fp32 input).
+struct Mfma16wPlan {
+    int inst, ckb;
+    int data[48];
+};
+bool plan_mfma16w(const ConvParams &p, const PackGeom &g, Mfma16wPlan *out);
+hipError_t launch_mfma16w(const ConvParams &p, const Mfma16wPlan &plan, hipStream_t s, const char **name);
+
 // 4x4x1 MFMA kernel (weights held in registers); plan is opaque to the caller.
 struct Mfma4Plan {
     int inst;        // index of the kernel instance

@@ -544,11 +544,12 @@ struct PlanKeyHash {
     }
 };
 struct Plan {
-    int kind;  // 0 none, 16, 4
+    int kind;  // 0 none, 32 (bf16), 17 (resident filters), 16, 4
     int idx;
     Tile16 t16;
     Mfma4Plan p4;
     MfmaB16Plan pb;
+    Mfma16wPlan pw;
 };
 
 const Plan &get_plan(const ConvParams &p, const PackGeom &g) {
@@ -559,6 +560,7 @@ const Plan &get_plan(const ConvParams &p, const PackGeom &g) {
     if (it != cache.end()) return it->second;
     Plan pl{};
     if (plan_mfma_bf16(p, g, &pl.pb)) pl.kind = 32;
+    else if (plan_mfma16w(p, g, &pl.pw)) pl.kind = 17;
     else if (plan16(p, g, &pl.idx, &pl.t16)) pl.kind = 16;
     else if (plan_mfma4(p, g, &pl.p4)) pl.kind = 4;
     return cache.emplace(k, pl).first->second;
@@ -579,6 +581,7 @@ hipError_t launch_mfma(const ConvParams &p, const PackGeom &g, hipStream_t s, co
         return p.in_bf16 ? launch16_cfg<uint16_t>(pl.idx, p, pl.t16, s) : launch16_cfg<float>(pl.idx, p, pl.t16, s);
     }
     if (pl.kind == 32) return launch_mfma_bf16(p, g, pl.pb, s, name);
+    if (pl.kind == 17) return launch_mfma16w(p, pl.pw, s, name);
     if (pl.kind == 4) return launch_mfma4(p, pl.p4, s, name);
     return hipErrorNotSupported;
 }

@@ -1,0 +1,502 @@
+// Per-group implicit-GEMM grouped convolution, 3x3, with the group's filter
+// tile resident in LDS and wave-private input tiles.
+//
+// Same contraction as conv_mfma16 (the convolution stage of Algorithm 1,
+// arXiv 2006.09791, with the paper's input and output reshapes fused in), but
+// organised for layers whose whole job is a few microseconds of matrix-core
+// work: one wave per SIMD, every wave owns 16*MI filters x 16*NI output pixels
+// for the whole reduction, and after the weights have landed no wave ever
+// waits for another one.
+//
+//   * The block's 16*MI filters (all CPG channels, 9 taps) are copied once
+//     from the packed matrix-core section into LDS, in MFMA A-operand order.
+//     The k-steps of the first chunk are committed first so that the first
+//     MFMA does not wait for the rest; the rest follows behind one more
+//     barrier after the first chunk has been multiplied.
+//   * Each wave stages the input rows of its own pixel tile in a private
+//     two-stage LDS ring (zero halo columns, rows outside the image arrive as
+//     zeros from the buffer loads), two chunks ahead through registers.
+//     LDS operations of one wave execute in order, so the ring needs no
+//     barrier.
+#include <cstdlib>
+#include <cstring>
+
+#include "conv_common.h"
+
+namespace gspc {
+
+constexpr int kTmaxW = 4;    // input staging slots (16 bytes per lane each) per chunk
+constexpr int kWmaxW = 20;   // weight staging slots (16 bytes per thread each), whole reduction
+
+struct Tile16w {
+    int NB, TH, IHt;         // images, output rows per wave tile; staged input rows
+    int LW, IMG, PLANE, XO;  // LDS row pitch, floats per image / per channel, column of input col 0
+    int nchunks;             // chunks of 4*CKB channels
+    int row_blocks, img_blocks, oc_blocks, wave_tiles;
+    int tpr_log2;            // lanes per staged row (log2), 16 bytes per lane
+    int tasks, xslots;       // staged rows per chunk, rows per lane per chunk
+    int wslots;              // weight slots in total (the first chunk's count is static)
+    int ksteps, mtiles;      // geometry of the packed weight section
+    int w_floats, stage_floats;
+    unsigned m_IHt, m_NB, m_ppi, m_Wout, m_rowb, m_ocb;
+    unsigned x_bytes, w_bytes, y_bytes;
+};
+
+#ifdef GSPC_PHASE_TIMING
+__device__ unsigned long long g_phase_w[8 * 4096];
+#define GSPC_STAMPW(i)                                                                     \
+    if (threadIdx.x == 0) {                                                                \
+        const unsigned bid = blockIdx.x + blockIdx.y * gridDim.x;                          \
+        if (bid < 4096) g_phase_w[bid * 8 + (i)] = __builtin_amdgcn_s_memrealtime();       \
+    }
+#else
+#define GSPC_STAMPW(i)
+#endif
+
+template <int MI, int NI, int S, int CKB, typename TIN>
+__global__ __launch_bounds__(256) void conv_mfma16w(ConvParams p, Tile16w t) {
+    GSPC_STAMPW(0)
+    constexpr int NT = 256, TAPS = 9, CK = 4 * CKB, KCHUNK = CKB * TAPS, ES = (int)sizeof(TIN);
+    constexpr int TMAX = kTmaxW, WMAX = kWmaxW;
+    constexpr int W0 = (KCHUNK * MI * 16 + NT - 1) / NT;   // weight slots the first chunk needs
+    extern __shared__ f32x4 smem4[];
+    float *smem = reinterpret_cast<float *>(smem4);
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const unsigned j = fast_div(blockIdx.y, t.m_ocb);
+    const int ob = blockIdx.y - j * t.oc_blocks;
+    const int wt = blockIdx.x * 4 + wave;      // this wave's pixel tile
+    const bool live = wt < t.wave_tiles;       // a dead wave loads zeros and stores nothing
+    const unsigned ib = fast_div(live ? wt : 0, t.m_rowb);
+    const int rb = (live ? wt : 0) - ib * t.row_blocks;
+    const int n0 = ib * t.NB, oh0 = rb * t.TH, ih0 = oh0 * S - p.pad;
+    const int ppi = t.TH * p.Wout, tot = t.NB * ppi;
+    const unsigned HW = p.H * p.W;
+
+    const __amdgpu_buffer_rsrc_t rx = make_rsrc(p.x, t.x_bytes);
+    const __amdgpu_buffer_rsrc_t rw = make_rsrc(p.wm, t.w_bytes);
+
+    // ---- weights: thread tid copies 16-byte unit k*256 + tid of the block's
+    // [k-step][MI][64] array; a slot of 256 units covers 16/MI k-steps.
+    constexpr unsigned kStepsPerSlot = NT / (MI * 16);
+    const unsigned wrow = t.mtiles * 64 * 4;   // bytes per k-step of the packed section
+    const unsigned wblk = ((j * t.ksteps * t.mtiles + ob * MI) * 64) * 4;
+    const unsigned wvoff = (tid / (MI * 16)) * wrow + (tid % (MI * 16)) * 16;
+    // Every slot is always requested (slots past the end get the out-of-range
+    // offset and cost no memory traffic): straight-line issue lets the compiler
+    // count exactly how many loads may stay in flight at each wait.
+    f32x4 pw[WMAX];
+    auto fetch_w = [&](int lo, int hi) __attribute__((always_inline)) {
+#pragma unroll
+        for (int k = 0; k < WMAX; ++k)
+            if (k >= lo && k < hi)
+                pw[k] = __builtin_bit_cast(
+                    f32x4, __builtin_amdgcn_raw_buffer_load_b128(rw, k < t.wslots ? wvoff : kOob,
+                                                                 wblk + k * kStepsPerSlot * wrow, 0));
+    };
+    auto commit_w = [&](int lo, int hi) __attribute__((always_inline)) {
+#pragma unroll
+        for (int k = 0; k < WMAX; ++k)
+            if (k >= lo && k < hi) smem4[k * NT + tid] = pw[k];
+    };
+
+    // ---- private input ring: wave w owns two stages -------------------------
+    // (a stage ends with a 16-byte spare slot that absorbs the writes of idle lanes)
+    float *ring = smem + t.w_floats + wave * (2 * t.stage_floats);
+    const unsigned spare = (t.stage_floats - 4) * 4;   // byte offset of the spare slot in a stage
+    const int rpp = 64 >> t.tpr_log2;
+    const int row0 = lane >> t.tpr_log2, colv = lane & ((1 << t.tpr_log2) - 1);
+    unsigned xoff[TMAX], xlds[TMAX];
+#pragma unroll
+    for (int k = 0; k < TMAX; ++k) {
+        const int task = row0 + k * rpp;
+        xoff[k] = kOob;
+        xlds[k] = spare;
+        if (k < t.xslots && task < t.tasks && colv * 4 < p.W) {
+            const int cimg = fast_div(task, t.m_IHt), r = task - cimg * t.IHt;
+            const int c = fast_div(cimg, t.m_NB), img = cimg - c * t.NB;
+            const int ih = ih0 + r, n = n0 + img;
+            xlds[k] = (c * t.PLANE + img * t.IMG + r * t.LW + t.XO + colv * 4) * 4;
+            if (live && n < p.N && ih >= 0 && ih < p.H)
+                xoff[k] = (((n * p.Cin + j * p.CPG + c) * p.H + ih) * p.W + colv * 4) * ES;
+        }
+    }
+    f32x4 pin0[TMAX], pin1[TMAX];
+    auto fetch_x = [&](int chunk, f32x4 (&pin)[TMAX]) __attribute__((always_inline)) {
+        const unsigned so = chunk * CK * HW * ES;
+        const bool on = chunk < t.nchunks;
+#pragma unroll
+        for (int k = 0; k < TMAX; ++k) pin[k] = buf_load_in<TIN>(rx, on ? xoff[k] : kOob, so, 1);
+    };
+    auto commit_x = [&](int stage, const f32x4 (&pin)[TMAX]) __attribute__((always_inline)) {
+        char *bb = reinterpret_cast<char *>(ring) + (stage ? t.stage_floats * 4 : 0);
+#pragma unroll
+        for (int k = 0; k < TMAX; ++k)
+            if (k < t.xslots) *reinterpret_cast<f32x4 *>(bb + xlds[k]) = pin[k];
+    };
+
+    // First chunk's weights and input, then the second chunk's input.
+    fetch_w(0, W0);
+    fetch_x(0, pin0);
+    fetch_x(1, pin1);
+    GSPC_STAMPW(1)
+
+    // ---- per-lane pixel coordinates ----------------------------------------
+    int base[NI];
+    unsigned ooff[NI];   // byte offset of this lane's first output element, or kOob
+    const unsigned HWo = p.Hout * p.Wout;
+#pragma unroll
+    for (int ni = 0; ni < NI; ++ni) {
+        const int q = ni * 16 + (lane & 15);
+        const int qq = q < tot ? q : 0;
+        const int img = fast_div(qq, t.m_ppi), rem = qq - img * ppi;
+        const int r = fast_div(rem, t.m_Wout), col = rem - r * p.Wout;
+        base[ni] = (lane >> 4) * t.PLANE + img * t.IMG + r * S * t.LW + (t.XO - p.pad) + col * S;
+        const int n = n0 + img, oh = oh0 + r;
+        ooff[ni] = (live && q < tot && n < p.N && oh < p.Hout)
+                       ? (((unsigned)n * p.Cout + j * p.KPG + 4 * (lane >> 4)) * HWo + oh * p.Wout + col) * 4
+                       : kOob;
+    }
+
+    f32x4 acc[MI][NI];
+#pragma unroll
+    for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+        for (int ni = 0; ni < NI; ++ni) acc[mi][ni] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    // Halo columns of both stages are never written by the staging: clear once.
+    {
+        const int rows = CK * t.NB * t.IHt;
+        const int right = t.XO + p.W;
+        for (int i = lane; i < 2 * rows; i += 64) {
+            const int b = i >= rows, rr = i - b * rows;
+            const int cimg = fast_div(rr, t.m_IHt), r = rr - cimg * t.IHt;
+            const int c = fast_div(cimg, t.m_NB), img = cimg - c * t.NB;
+            float *row = ring + b * t.stage_floats + c * t.PLANE + img * t.IMG + r * t.LW;
+            for (int x = 0; x < t.XO; ++x) row[x] = 0.f;
+            for (int x = right; x < t.LW; ++x) row[x] = 0.f;
+        }
+    }
+
+    // The reduction of a chunk is a sequence of R = 3*CKB rows (one filter row of
+    // one 4-channel block: 3 k-steps).  The operands of row i+1 are read from
+    // LDS while row i is multiplied (two register sets), across chunk borders
+    // too, so that with one wave per SIMD the matrix core does not wait for LDS.
+    constexpr int R = 3 * CKB;
+    float opa[2][3][MI], opb[2][3][NI];
+    auto load_row = [&](int ch, int row, float (&a)[3][MI], float (&b)[3][NI]) __attribute__((always_inline)) {
+        const int cb = row / 3, kh = row - 3 * cb;
+        const float *xrow = ring + (ch & 1) * t.stage_floats + cb * 4 * t.PLANE + kh * t.LW;
+        const float *ws = smem + (ch * KCHUNK + row * 3) * (MI * 64) + lane;
+#pragma unroll
+        for (int kw = 0; kw < 3; ++kw) {
+#pragma unroll
+            for (int mi = 0; mi < MI; ++mi) a[kw][mi] = ws[(kw * MI + mi) * 64];
+#pragma unroll
+            for (int ni = 0; ni < NI; ++ni) b[kw][ni] = xrow[base[ni] + kw];
+        }
+    };
+    auto mfma_row = [&](const float (&a)[3][MI], const float (&b)[3][NI]) __attribute__((always_inline)) {
+#pragma unroll
+        for (int kw = 0; kw < 3; ++kw)
+#pragma unroll
+            for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+                for (int ni = 0; ni < NI; ++ni)
+                    acc[mi][ni] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[kw][mi], b[kw][ni], acc[mi][ni], 0, 0, 0);
+    };
+
+    // ---- first chunk, then the rest of the weights --------------------------
+    commit_w(0, W0);
+    commit_x(0, pin0);
+    __syncthreads();
+    GSPC_STAMPW(2)
+    // The other weights are requested while the first chunk is multiplied, a few
+    // loads per row: the CU's vector memory path takes 16 cycles per
+    // 16-byte-per-lane load and all four waves share it, so a burst of loads
+    // would hold up the MFMAs queued behind it.
+    {
+        constexpr int PER = (WMAX - W0 + R - 1) / R;
+        load_row(0, 0, opa[0], opb[0]);
+#pragma unroll
+        for (int i = 0; i < R; ++i) {
+            fetch_w(W0 + i * PER, W0 + (i + 1) * PER);
+            if (i + 1 < R) load_row(0, i + 1, opa[(i + 1) & 1], opb[(i + 1) & 1]);
+            __builtin_amdgcn_sched_barrier(0);   // operand reads first, then the MFMAs they overlap with
+            mfma_row(opa[i & 1], opb[i & 1]);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    }
+    fetch_x(2, pin0);
+    GSPC_STAMPW(3)
+    commit_w(W0, t.wslots);
+    __syncthreads();
+    GSPC_STAMPW(4)
+#ifdef GSPC_PHASE_TIMING
+    const unsigned long long clk0 = __builtin_amdgcn_s_memtime();
+#endif
+    constexpr int P1 = R & 1;   // register set that holds row 0 of an odd chunk
+    if (t.nchunks > 1) {
+        commit_x(1, pin1);
+        load_row(1, 0, opa[P1], opb[P1]);
+    }
+
+    // Steady state, no barriers: iteration ch multiplies chunk ch out of stage
+    // ch&1; before its last row chunk ch+1 moves registers -> the other stage,
+    // chunk ch+2 is requested from global memory at its start (two register
+    // sets pin0 / pin1).
+    for (int ch = 1; ch < t.nchunks; ch += 2) {
+        // odd chunk: pin1 is free (chunk ch is in LDS), pin0 holds chunk ch+1
+        fetch_x(ch + 2, pin1);
+#pragma unroll
+        for (int i = 0; i < R; ++i) {
+            if (i + 1 < R) {
+                load_row(ch, i + 1, opa[(P1 + i + 1) & 1], opb[(P1 + i + 1) & 1]);
+            } else {
+                if (ch + 1 < t.nchunks) commit_x(0, pin0);
+                load_row(ch + 1, 0, opa[(P1 + i + 1) & 1], opb[(P1 + i + 1) & 1]);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            mfma_row(opa[(P1 + i) & 1], opb[(P1 + i) & 1]);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        if (ch + 1 < t.nchunks) {
+            // even chunk: pin0 is free, pin1 holds chunk ch+2
+            fetch_x(ch + 3, pin0);
+#pragma unroll
+            for (int i = 0; i < R; ++i) {
+                if (i + 1 < R) {
+                    load_row(ch + 1, i + 1, opa[(i + 1) & 1], opb[(i + 1) & 1]);
+                } else {
+                    if (ch + 2 < t.nchunks) commit_x(1, pin1);
+                    load_row(ch + 2, 0, opa[(i + 1) & 1], opb[(i + 1) & 1]);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+                mfma_row(opa[i & 1], opb[i & 1]);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+    }
+
+    GSPC_STAMPW(5)
+#ifdef GSPC_PHASE_TIMING
+    if (threadIdx.x == 0) {
+        const unsigned bid = blockIdx.x + blockIdx.y * gridDim.x;
+        if (bid < 4096) g_phase_w[bid * 8 + 7] = __builtin_amdgcn_s_memtime() - clk0;
+    }
+#endif
+    // ---- epilogue: optional residual and ReLU, NCHW store -------------------
+    // Register r of tile (mi, ni) is filter 16*(tile row) + 4*(lane/16) + r at
+    // this lane's pixel; the 4*(lane/16) part already sits in ooff.
+    const __amdgpu_buffer_rsrc_t ry = make_rsrc(p.y, t.y_bytes);
+    const unsigned oc0 = ob * MI * 16;
+    if (p.res) {
+        const __amdgpu_buffer_rsrc_t rr = make_rsrc(p.res, t.y_bytes);
+#pragma unroll
+        for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+            for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+                for (int r = 0; r < 4; ++r)
+                    acc[mi][ni][r] += __uint_as_float(
+                        __builtin_amdgcn_raw_buffer_load_b32(rr, ooff[ni], (oc0 + mi * 16 + r) * HWo * 4, 0));
+    }
+#pragma unroll
+    for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+        for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                float v = acc[mi][ni][r];
+                if (p.relu) v = fmaxf(v, 0.f);
+                __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(v), ry, ooff[ni],
+                                                      (oc0 + mi * 16 + r) * HWo * 4, 0);
+            }
+    GSPC_STAMPW(6)
+}
+
+#ifdef GSPC_PHASE_TIMING
+extern "C" int gspc_debug_phases_w(unsigned long long *out, int n) {
+    return (int)hipMemcpyFromSymbol(out, HIP_SYMBOL(g_phase_w), sizeof(unsigned long long) * n);
+}
+#endif
+
+// ---------------------------------------------------------------------------
+// Host side
+// ---------------------------------------------------------------------------
+namespace {
+
+constexpr size_t kLdsMaxW = 160 * 1024;
+
+struct CfgW {
+    int MI, NI;
+};
+// Largest wave tile first.
+const CfgW kCfgW[] = {{2, 4}, {2, 2}, {1, 4}, {1, 2}, {1, 1}};
+constexpr int kNumCfgW = sizeof(kCfgW) / sizeof(kCfgW[0]);
+
+// Worst bank multiplicity (32 banks of 4 bytes) of a B-operand read for a
+// candidate channel pitch.
+int bank_cost_w(const ConvParams &p, const Tile16w &t, int plane) {
+    int worst = 0;
+    for (int half = 0; half < 2; ++half) {
+        int cnt[32] = {0};
+        for (int l = 32 * half; l < 32 * half + 32; ++l) {
+            int q = l & 15;
+            const int ppi = t.TH * p.Wout;
+            if (q >= t.NB * ppi) q = 0;
+            const int img = q / ppi, rem = q % ppi, r = rem / p.Wout, col = rem % p.Wout;
+            const int a = (l >> 4) * plane + img * t.IMG + r * p.stride * t.LW + col * p.stride;
+            ++cnt[a & 31];
+        }
+        for (int b = 0; b < 32; ++b) worst = cnt[b] > worst ? cnt[b] : worst;
+    }
+    return worst;
+}
+
+bool planW_cfg(const ConvParams &p, const PackGeom &g, const CfgW &c, int ckb, Tile16w *out) {
+    const int MB = 16 * c.MI, PW = 16 * c.NI, CK = 4 * ckb;
+    if (g.KPG % MB || g.CPG % CK) return false;
+    Tile16w t{};
+    if (!split_pixels(p, PW, &t.NB, &t.TH)) return false;
+    t.IHt = (t.TH - 1) * p.stride + 3;
+    t.XO = 4 * ((p.pad + 3) / 4);
+    t.LW = round_up(t.XO + p.W + p.pad, 4);
+    t.IMG = t.IHt * t.LW;
+    const int plane0 = round_up(t.NB * t.IMG, 4);
+    int best_pad = 0, best_cost = 1 << 30;
+    for (int pad = 0; pad < 32; pad += 4) {
+        const int cost = bank_cost_w(p, t, plane0 + pad);
+        if (cost < best_cost) {
+            best_cost = cost;
+            best_pad = pad;
+        }
+    }
+    t.PLANE = plane0 + best_pad;
+    const int cols = p.W / 4;
+    t.tpr_log2 = 0;
+    while ((1 << t.tpr_log2) < cols) ++t.tpr_log2;
+    if ((1 << t.tpr_log2) > 64) return false;
+    const int rpp = 64 >> t.tpr_log2;
+    t.tasks = CK * t.NB * t.IHt;
+    t.xslots = (t.tasks + rpp - 1) / rpp;
+    if (t.xslots > kTmaxW) return false;
+    t.ksteps = g.ksteps;
+    t.mtiles = g.mtiles;
+    t.nchunks = g.CPG / CK;
+    const int units = g.ksteps * c.MI * 16;            // 16-byte units of the block's weights
+    t.wslots = (units + 255) / 256;
+    if (t.wslots > kWmaxW) return false;
+    if (t.wslots < (ckb * 9 * c.MI * 16 + 255) / 256) return false;
+    t.w_floats = t.wslots * 256 * 4;
+    t.stage_floats = CK * t.PLANE + 4;
+    const size_t lds = ((size_t)t.w_floats + 8 * (size_t)t.stage_floats) * sizeof(float);
+    if (lds > kLdsMaxW) return false;
+    t.row_blocks = (p.Hout + t.TH - 1) / t.TH;
+    t.img_blocks = (p.N + t.NB - 1) / t.NB;
+    t.oc_blocks = g.KPG / MB;
+    const long wt = (long)t.row_blocks * t.img_blocks;
+    if (wt > 1000000000L || p.groups * t.oc_blocks > 65535) return false;
+    t.wave_tiles = (int)wt;
+    t.m_IHt = div_magic(t.IHt);
+    t.m_NB = div_magic(t.NB);
+    t.m_ppi = div_magic(t.TH * p.Wout);
+    t.m_Wout = div_magic(p.Wout);
+    t.m_rowb = div_magic(t.row_blocks);
+    t.m_ocb = div_magic(t.oc_blocks);
+    const double xb = (double)p.N * p.Cin * p.H * p.W * (p.in_bf16 ? 2 : 4);
+    const double yb = (double)p.N * p.Cout * p.Hout * p.Wout * 4;
+    const double wb = (double)p.groups * g.ksteps * g.mtiles * 256;
+    if (xb >= (double)kOob || yb >= (double)kOob || wb >= (double)kOob) return false;
+    t.x_bytes = (unsigned)xb;
+    t.y_bytes = (unsigned)yb;
+    t.w_bytes = (unsigned)wb;
+    if ((double)wt * t.row_blocks >= 4.0e9 || (double)p.groups * t.oc_blocks * t.oc_blocks >= 4.0e9 ||
+        t.tasks >= 65536 || t.TH * p.Wout >= 65536)
+        return false;
+    *out = t;
+    return true;
+}
+
+size_t lds_bytes_w(const Tile16w &t) {
+    return ((size_t)t.w_floats + 8 * (size_t)t.stage_floats) * sizeof(float);
+}
+
+template <int MI, int NI, int S, int CKB>
+hipError_t launchW_inst(const ConvParams &p, const Tile16w &t, hipStream_t s) {
+    const size_t lds = lds_bytes_w(t);
+    dim3 grid((t.wave_tiles + 3) / 4, p.groups * t.oc_blocks);
+    auto kern = conv_mfma16w<MI, NI, S, CKB, float>;
+    if (lds > 64 * 1024) {
+        static thread_local bool raised = false;   // per instantiation and thread
+        if (!raised) {
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsMaxW);
+            if (e != hipSuccess) return e;
+            raised = true;
+        }
+    }
+    hipLaunchKernelGGL(kern, grid, dim3(256), lds, s, p, t);
+    return hipGetLastError();
+}
+
+template <int MI, int NI>
+hipError_t launchW_shape(int stride, int ckb, const ConvParams &p, const Tile16w &t, hipStream_t s) {
+    if (stride == 1) return ckb == 2 ? launchW_inst<MI, NI, 1, 2>(p, t, s) : launchW_inst<MI, NI, 1, 1>(p, t, s);
+    return ckb == 2 ? launchW_inst<MI, NI, 2, 2>(p, t, s) : launchW_inst<MI, NI, 2, 1>(p, t, s);
+}
+
+}  // namespace
+
+bool plan_mfma16w(const ConvParams &p, const PackGeom &g, Mfma16wPlan *out) {
+    static const bool off = std::getenv("GSPC_NO_RESIDENT") != nullptr;   // tuning aid
+    if (off || g.variant != kMfma16 || !p.wm || p.in_bf16 || p.KH != 3 || p.KW != 3 ||
+        (p.stride != 1 && p.stride != 2) || p.W % 4 || g.CPG % 4 || g.CPGp != g.CPG)
+        return false;
+    static const char *force = std::getenv("GSPC_TILEW");
+    const int ckb = g.CPG % 8 == 0 ? 2 : 1;
+    int best = -1;
+    long best_waves = -1;
+    Tile16w bt{};
+    for (int i = 0; i < kNumCfgW; ++i) {
+        Tile16w t;
+        if (force && std::atoi(force) != i) continue;
+        if (!planW_cfg(p, g, kCfgW[i], ckb, &t)) continue;
+        const long waves = (long)t.wave_tiles * t.oc_blocks * p.groups;
+        if (waves >= 4 * kNumCU) {   // every SIMD has a wave: take the largest such tile
+            best = i;
+            bt = t;
+            break;
+        }
+        if (waves > best_waves) {
+            best_waves = waves;
+            best = i;
+            bt = t;
+        }
+    }
+    if (best < 0) return false;
+    out->inst = best;
+    out->ckb = ckb;
+    static_assert(sizeof(Tile16w) <= sizeof(out->data), "plan storage too small");
+    std::memcpy(out->data, &bt, sizeof(bt));
+    return true;
+}
+
+hipError_t launch_mfma16w(const ConvParams &p, const Mfma16wPlan &plan, hipStream_t s, const char **name) {
+    Tile16w t;
+    std::memcpy(&t, plan.data, sizeof(t));
+    const CfgW &c = kCfgW[plan.inst];
+    *name = intern_name("conv_mfma16w<" + std::to_string(c.MI) + "," + std::to_string(c.NI) + "," +
+                        std::to_string(p.stride) + "," + std::to_string(plan.ckb) + ",f32>");
+    switch (plan.inst) {
+    case 0: return launchW_shape<2, 4>(p.stride, plan.ckb, p, t, s);
+    case 1: return launchW_shape<2, 2>(p.stride, plan.ckb, p, t, s);
+    case 2: return launchW_shape<1, 4>(p.stride, plan.ckb, p, t, s);
+    case 3: return launchW_shape<1, 2>(p.stride, plan.ckb, p, t, s);
+    case 4: return launchW_shape<1, 1>(p.stride, plan.ckb, p, t, s);
+    }
+    return hipErrorNotSupported;
+}
+
+}  // namespace gspc
