@@ -55,6 +55,9 @@ def main():
     ap.add_argument("--sweep", choices=["wrn", "resnet_bf16", "depthwise", "latency"],
                     help="instead of the headline step, time every layer of a configuration family "
                          "and print one JSON line with a row per layer")
+    ap.add_argument("--fusion", action="store_true",
+                    help="let the timed step fuse runs of grouped layers (one kernel per run); off by "
+                         "default: with five chains in flight the separate small kernels overlap better")
     ap.add_argument("--serial", action="store_true",
                     help="run the five chains of a step one after the other on one stream")
     args = ap.parse_args()
@@ -156,6 +159,10 @@ def main():
             b.gspc_run_layer_chain(lc)
         b.gspc_set_stream(stream)
 
+    # Depth fusion shortens a chain that runs alone (see per_g below), but its
+    # kernels hold a whole CU's LDS; with five chains in flight the separate
+    # small kernels fill each other's gaps and the step is faster without it.
+    b.gspc_set_chain_fusion(1 if args.fusion else 0)
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -168,7 +175,8 @@ def main():
     ms_per_step = sec / args.steps * 1e3
     value = macs_step * args.steps / sec / 1e9
 
-    # ---- per-g latency (outside the timed region) --------------------------
+    # ---- per-g latency (outside the timed region), library defaults ---------
+    b.gspc_set_chain_fusion(1)
     per_g = {}
     for g, ch, lc in zip(GROUPS, chains, lcs):
         reps = max(5, min(50, args.steps))
@@ -184,6 +192,7 @@ def main():
     roofline = None
     kernels = {}
     if not args.no_roofline:
+        b.gspc_set_chain_fusion(0)   # this leg times single layers
         reps = 20
         for ch, (packed, bufs) in zip(chains, keep):
             seen = {}
@@ -267,7 +276,8 @@ def main():
         "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": "WRN-40-2-style CIFAR stack, 3x32x32 input, every 3x3 conv grouped, "
                                "fp32, N=64, one pass per g in {1,2,4,8,16} per step",
-                   "batch": BATCH, "groups": list(GROUPS), "gmac_per_step": round(macs_step / 1e9, 3)},
+                   "batch": BATCH, "groups": list(GROUPS), "gmac_per_step": round(macs_step / 1e9, 3),
+                   "streams": 1 if args.serial else len(GROUPS), "chain_fusion_in_step": bool(args.fusion)},
         "per_g": per_g,
         "roofline": roofline,
         "cpu_baseline": cpu,

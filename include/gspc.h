@@ -172,6 +172,18 @@ typedef struct gspc_layer {
  * the feature off and releases them, gspc_set_graph_mode(1) turns it back on. */
 int gspc_set_graph_mode(int on);
 
+/* Depth fusion of layer chains (Section 2.1 / Eq. 1: a grouped convolution only
+ * mixes the channels of one group).  By default gspc_run_layer_chain evaluates a
+ * run of consecutive fp32 CONV steps that share N, C, H, W and groups >= 2,
+ * with 3x3 kernels, stride 1, pad 1, Cin = Cout and at most 32 channels per
+ * group, in one kernel per run: one workgroup per (image, group) keeps the
+ * activations of the run in on-chip memory.  Every buffer ends up with exactly
+ * the contents the step-by-step execution leaves in it (the last value
+ * written to it), up to floating-point summation order.  gspc_set_chain_fusion(0)
+ * turns the feature off for the calling thread, (1) back on.  Runs with
+ * per-layer timing are never fused. */
+int gspc_set_chain_fusion(int on);
+
 /* Runs the steps in order on the selected stream.  act_bufs[i] (dev) holds
  * act_bytes[i] bytes; every step is validated against those sizes before
  * anything is launched (GSPC_ERR_SPACE / GSPC_ERR_ARG).  A CONV whose handle

@@ -24,7 +24,7 @@ EXPORTS = [
     "gspc_version", "gspc_set_stream", "gspc_last_error", "gspc_output_dims", "gspc_layer_macs",
     "gspc_packed_weight_bytes", "gspc_pack_weights", "gspc_unpack_weights", "gspc_packed_free",
     "gspc_packed_info", "gspc_pack_input_bf16", "gspc_conv2d_grouped", "gspc_force_path",
-    "gspc_last_path", "gspc_last_kernel", "gspc_set_graph_mode", "gspc_run_layer_chain",
+    "gspc_last_path", "gspc_last_kernel", "gspc_set_graph_mode", "gspc_set_chain_fusion", "gspc_run_layer_chain",
 ]
 
 
@@ -88,6 +88,8 @@ def load():
     lib.gspc_last_path.restype = i
     lib.gspc_set_graph_mode.restype = i
     lib.gspc_set_graph_mode.argtypes = [i]
+    lib.gspc_set_chain_fusion.restype = i
+    lib.gspc_set_chain_fusion.argtypes = [i]
     lib.gspc_last_kernel.restype = ctypes.c_char_p
     lib.gspc_run_layer_chain.restype = i
     lib.gspc_run_layer_chain.argtypes = [ctypes.POINTER(GspcLayer), i, ctypes.POINTER(vp),
@@ -215,6 +217,10 @@ def gspc_force_path(path):
 
 def gspc_set_graph_mode(on):
     _check(load().gspc_set_graph_mode(1 if on else 0))
+
+
+def gspc_set_chain_fusion(on):
+    _check(load().gspc_set_chain_fusion(1 if on else 0))
 
 
 def gspc_last_path():

@@ -4,6 +4,7 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <memory>
 #include <new>
 #include <unordered_map>
 #include <vector>
@@ -18,6 +19,7 @@ thread_local int t_force_path = GSPC_PATH_AUTO;
 thread_local int t_last_path = GSPC_PATH_AUTO;
 thread_local const char *t_last_kernel = "";
 thread_local int t_graph_mode = 1;
+thread_local int t_fusion = 1;
 
 // Recorded layer chains, per thread, keyed by everything a replay depends on.
 struct ChainGraph {
@@ -41,7 +43,7 @@ uint64_t fnv(uint64_t h, const void *data, size_t n) {
 }
 
 uint64_t chain_key(const gspc_layer_t *layers, int n_layers, void *const *bufs, int n_bufs,
-                   hipStream_t stream, int force_path) {
+                   hipStream_t stream, int force_path, int fusion) {
     uint64_t h = 1469598103934665603ull;
     for (int i = 0; i < n_layers; ++i) {
         const gspc_layer_t &L = layers[i];
@@ -56,6 +58,7 @@ uint64_t chain_key(const gspc_layer_t *layers, int n_layers, void *const *bufs, 
     h = fnv(h, bufs, sizeof(void *) * n_bufs);
     h = fnv(h, &stream, sizeof(stream));
     h = fnv(h, &force_path, sizeof(force_path));
+    h = fnv(h, &fusion, sizeof(fusion));
     return h;
 }
 
@@ -321,6 +324,11 @@ int gspc_set_graph_mode(int on) {
     return GSPC_OK;
 }
 
+int gspc_set_chain_fusion(int on) {
+    t_fusion = on ? 1 : 0;
+    return GSPC_OK;
+}
+
 int gspc_last_path(void) { return t_last_path; }
 const char *gspc_last_kernel(void) { return t_last_kernel; }
 
@@ -420,19 +428,54 @@ int gspc_run_layer_chain(const gspc_layer_t *layers, int n_layers, void *const *
     };
 
     if (!per_layer_ms) {
+        // Steps of the untimed path: single layers, or fused runs of grouped layers.
+        struct Step {
+            int first, count;
+            gspc::FusedPlan *plan;
+        };
+        std::vector<Step> steps;
+        std::vector<std::unique_ptr<gspc::FusedPlan>> plans;
+        for (int i = 0; i < n_layers;) {
+            int covered = 0;
+            if (t_fusion && t_force_path == GSPC_PATH_AUTO) {
+                auto pl = std::make_unique<gspc::FusedPlan>();
+                covered = gspc::plan_fused_run(layers, i, n_layers - i, act_bufs, pl.get());
+                if (covered > 0) {
+                    steps.push_back({i, covered, pl.get()});
+                    plans.push_back(std::move(pl));
+                }
+            }
+            if (covered == 0) {
+                steps.push_back({i, 1, nullptr});
+                covered = 1;
+            }
+            i += covered;
+        }
+        auto run_steps = [&]() -> int {
+            for (const Step &st : steps) {
+                if (st.plan) {
+                    const hipError_t e = gspc::launch_fused_run(*st.plan, t_stream, &t_last_kernel);
+                    if (e != hipSuccess) return hip_fail(e, "fused run launch");
+                    t_last_path = GSPC_PATH_DIRECT;
+                } else {
+                    const int rc2 = launch_step(st.first);
+                    if (rc2 != GSPC_OK) return rc2;
+                }
+            }
+            return GSPC_OK;
+        };
         hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
         const bool try_graph = t_graph_mode && t_stream != nullptr && n_layers > 1 &&
                                hipStreamIsCapturing(t_stream, &cap) == hipSuccess &&
                                cap == hipStreamCaptureStatusNone;
         if (try_graph) {
-            const uint64_t key = chain_key(layers, n_layers, act_bufs, n_bufs, t_stream, t_force_path);
+            const uint64_t key = chain_key(layers, n_layers, act_bufs, n_bufs, t_stream, t_force_path, t_fusion);
             auto it = t_graphs.find(key);
             if (it == t_graphs.end()) {
                 hipGraph_t graph = nullptr;
                 hipGraphExec_t exec = nullptr;
                 if (hipStreamBeginCapture(t_stream, hipStreamCaptureModeThreadLocal) == hipSuccess) {
-                    int rc2 = GSPC_OK;
-                    for (int i = 0; i < n_layers && rc2 == GSPC_OK; ++i) rc2 = launch_step(i);
+                    const int rc2 = run_steps();
                     const hipError_t ee = hipStreamEndCapture(t_stream, &graph);
                     if (rc2 != GSPC_OK) {
                         if (graph) (void)hipGraphDestroy(graph);
@@ -456,9 +499,7 @@ int gspc_run_layer_chain(const gspc_layer_t *layers, int n_layers, void *const *
                 return GSPC_OK;
             }
         }
-        int rc = GSPC_OK;
-        for (int i = 0; i < n_layers && rc == GSPC_OK; ++i) rc = launch_step(i);
-        return rc;
+        return run_steps();
     }
 
     std::vector<hipEvent_t> ev(n_layers + 1);

@@ -109,6 +109,33 @@ struct Mfma4Plan {
 bool plan_mfma4(const ConvParams &p, const PackGeom &g, Mfma4Plan *out);
 hipError_t launch_mfma4(const ConvParams &p, const Mfma4Plan &plan, hipStream_t s, const char **name);
 
+// Fused run of consecutive grouped 3x3 layers (fused_kernels.hip).
+constexpr int kFuseMaxLayers = 16, kFuseMaxTiles = 3, kFuseMaxInputs = 3;
+struct FusedLayer {
+    const float *w;   // direct section of the layer's packed weights
+    float *y;         // HBM destination, or nullptr if a later layer of the run overwrites the buffer
+    short src, res, dst, relu;   // LDS tile indices (res, dst: -1 = none)
+};
+struct FusedRun {
+    int N, C, H, W, groups, CPG, KPGd;
+    int vec, XO, LW, PLANE, TILE, wfloats;   // tile geometry (floats); 16-byte global accesses allowed
+    int nlayers, ninputs, ntiles;
+    int rgroups, nitems;                     // groups of NI pixel runs per filter tile; wave items per layer
+    unsigned m_groups, m_rgroups, m_hw, m_w, m_hwq, m_wq;
+    const float *in_ptr[kFuseMaxInputs];
+    int in_tile[kFuseMaxInputs];
+    FusedLayer L[kFuseMaxLayers];
+};
+struct FusedPlan {
+    int core;     // pixel runs per wave item (template argument of the kernel)
+    int waves;    // waves per block (template argument of the kernel)
+    size_t lds;
+    FusedRun run;
+};
+// Number of leading layers of layers[first .. first+count) that one fused launch covers (0 = none).
+int plan_fused_run(const gspc_layer_t *layers, int first, int count, void *const *bufs, FusedPlan *out);
+hipError_t launch_fused_run(const FusedPlan &plan, hipStream_t s, const char **name);
+
 hipError_t launch_pack_weights(const float *w, const gspc_packed *h, hipStream_t s);
 hipError_t launch_unpack_weights(const gspc_packed *h, int which, float *w, hipStream_t s);
 hipError_t launch_cast_bf16(const float *in, size_t count, uint16_t *out, hipStream_t s);

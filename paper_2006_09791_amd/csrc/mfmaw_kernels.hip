@@ -23,6 +23,10 @@
 
 #include "conv_common.h"
 
+#ifndef GSPC_EXP
+#define GSPC_EXP 0
+#endif
+
 namespace gspc {
 
 constexpr int kTmaxW = 4;    // input staging slots (16 bytes per lane each) per chunk
@@ -92,7 +96,7 @@ __global__ __launch_bounds__(256) void conv_mfma16w(ConvParams p, Tile16w t) {
         for (int k = 0; k < WMAX; ++k)
             if (k >= lo && k < hi)
                 pw[k] = __builtin_bit_cast(
-                    f32x4, __builtin_amdgcn_raw_buffer_load_b128(rw, k < t.wslots ? wvoff : kOob,
+                    f32x4, __builtin_amdgcn_raw_buffer_load_b128(rw, k < (GSPC_EXP == 3 ? W0 : t.wslots) ? wvoff : kOob,
                                                                  wblk + k * kStepsPerSlot * wrow, 0));
     };
     auto commit_w = [&](int lo, int hi) __attribute__((always_inline)) {
@@ -125,7 +129,11 @@ __global__ __launch_bounds__(256) void conv_mfma16w(ConvParams p, Tile16w t) {
     f32x4 pin0[TMAX], pin1[TMAX];
     auto fetch_x = [&](int chunk, f32x4 (&pin)[TMAX]) __attribute__((always_inline)) {
         const unsigned so = chunk * CK * HW * ES;
+#if GSPC_EXP == 1
+        const bool on = chunk < 2;
+#else
         const bool on = chunk < t.nchunks;
+#endif
 #pragma unroll
         for (int k = 0; k < TMAX; ++k) pin[k] = buf_load_in<TIN>(rx, on ? xoff[k] : kOob, so, 1);
     };
@@ -140,6 +148,9 @@ __global__ __launch_bounds__(256) void conv_mfma16w(ConvParams p, Tile16w t) {
     fetch_w(0, W0);
     fetch_x(0, pin0);
     fetch_x(1, pin1);
+#if GSPC_EXP == 4
+    fetch_w(W0, WMAX);
+#endif
     GSPC_STAMPW(1)
 
     // ---- per-lane pixel coordinates ----------------------------------------
@@ -191,6 +202,9 @@ __global__ __launch_bounds__(256) void conv_mfma16w(ConvParams p, Tile16w t) {
         const float *ws = smem + (ch * KCHUNK + row * 3) * (MI * 64) + lane;
 #pragma unroll
         for (int kw = 0; kw < 3; ++kw) {
+#if GSPC_EXP == 2
+            if (ch > 1) continue;
+#endif
 #pragma unroll
             for (int mi = 0; mi < MI; ++mi) a[kw][mi] = ws[(kw * MI + mi) * 64];
 #pragma unroll
@@ -212,24 +226,40 @@ __global__ __launch_bounds__(256) void conv_mfma16w(ConvParams p, Tile16w t) {
     commit_x(0, pin0);
     __syncthreads();
     GSPC_STAMPW(2)
-    // The other weights are requested while the first chunk is multiplied, a few
-    // loads per row: the CU's vector memory path takes 16 cycles per
+#ifdef GSPC_PHASE_TIMING
+    const unsigned long long clkc0 = __builtin_amdgcn_s_memtime();
+#endif
+    // The other weights are requested while the first chunk is multiplied, one
+    // load per k-step or so: the CU's vector memory path takes 16 cycles per
     // 16-byte-per-lane load and all four waves share it, so a burst of loads
     // would hold up the MFMAs queued behind it.
     {
-        constexpr int PER = (WMAX - W0 + R - 1) / R;
+        constexpr int STEPS = 3 * R, PER = (WMAX - W0 + STEPS - 1) / STEPS;
         load_row(0, 0, opa[0], opb[0]);
 #pragma unroll
         for (int i = 0; i < R; ++i) {
-            fetch_w(W0 + i * PER, W0 + (i + 1) * PER);
             if (i + 1 < R) load_row(0, i + 1, opa[(i + 1) & 1], opb[(i + 1) & 1]);
             __builtin_amdgcn_sched_barrier(0);   // operand reads first, then the MFMAs they overlap with
-            mfma_row(opa[i & 1], opb[i & 1]);
-            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int kw = 0; kw < 3; ++kw) {
+#if GSPC_EXP != 4
+                fetch_w(W0 + (i * 3 + kw) * PER, W0 + (i * 3 + kw + 1) * PER);
+#endif
+#pragma unroll
+                for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+                    for (int ni = 0; ni < NI; ++ni)
+                        acc[mi][ni] = __builtin_amdgcn_mfma_f32_16x16x4f32(opa[i & 1][kw][mi], opb[i & 1][kw][ni],
+                                                                           acc[mi][ni], 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
+            }
         }
     }
     fetch_x(2, pin0);
     GSPC_STAMPW(3)
+#ifdef GSPC_PHASE_TIMING
+    const unsigned long long clkc1 = __builtin_amdgcn_s_memtime() - clkc0;
+#endif
     commit_w(W0, t.wslots);
     __syncthreads();
     GSPC_STAMPW(4)
@@ -283,7 +313,7 @@ __global__ __launch_bounds__(256) void conv_mfma16w(ConvParams p, Tile16w t) {
 #ifdef GSPC_PHASE_TIMING
     if (threadIdx.x == 0) {
         const unsigned bid = blockIdx.x + blockIdx.y * gridDim.x;
-        if (bid < 4096) g_phase_w[bid * 8 + 7] = __builtin_amdgcn_s_memtime() - clk0;
+        if (bid < 4096) g_phase_w[bid * 8 + 7] = ((__builtin_amdgcn_s_memtime() - clk0) & 0xffffffffull) | (clkc1 << 32);
     }
 #endif
     // ---- epilogue: optional residual and ReLU, NCHW store -------------------

@@ -27,6 +27,7 @@ def time_layers(shapes, dtype="f32", inner=10, reps=10, rotate=1):
     import torch
     dev = torch.device("cuda:0")
     b.gspc_set_stream()
+    b.gspc_set_chain_fusion(0)   # the chains below repeat one layer: time it as a single kernel
     rows = []
     for s in shapes:
         ho, wo = b.gspc_output_dims(s.H, s.W, s.KH, s.KW, s.stride, s.pad)
@@ -65,4 +66,5 @@ def time_layers(shapes, dtype="f32", inner=10, reps=10, rotate=1):
             "frac_hbm": round(nbytes / us / 1e3 / PEAK_HBM_GBS, 4),
         })
         del bufs, lc
+    b.gspc_set_chain_fusion(1)
     return rows
