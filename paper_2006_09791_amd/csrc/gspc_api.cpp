@@ -168,10 +168,10 @@ PackGeom make_pack_geom(int Cin, int Cout, int KH, int KW, int groups, int dtype
     else if (g.KPG % 4 == 0) g.variant = kMfma4;
     else g.variant = kMfmaNone;
     if (g.variant == kMfma16) {
-        g.ksub = mfma_ksub(g.variant);
+        g.ksub = 4;
         g.CPGp = round_up(g.CPG, g.ksub);
         g.ksteps = g.CPGp / g.ksub * KH * KW;
-        g.mtiles = g.KPG / g.variant;
+        g.mtiles = g.KPG / 16;
         g.mfma_bytes = (size_t)groups * g.mtiles * g.ksteps * 64 * sizeof(float);
     }
     g.mfma_offset = (g.direct_bytes + 255) / 256 * 256;

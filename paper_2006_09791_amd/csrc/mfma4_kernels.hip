@@ -7,7 +7,8 @@
 // gets the same four filters as A (lane l holds filter l%4), so one instruction
 // updates 4 filters x 64 pixels for one (c, kh, kw) of the convolution stage of
 // Algorithm 1 (arXiv 2006.09791).  The group's whole filter bank
-// (KPG x CPG x 9 values) lives in registers for the lifetime of a wave; the
+// (KPG x CPG x 9 values) lives in registers for the lifetime of a wave (it gets
+// there through LDS: one coalesced copy per block, then wide LDS reads); the
 // pixel operand comes from a zero-haloed LDS tile of the group's input slab.
 #include <cstdlib>
 #include <cstring>
@@ -45,17 +46,24 @@ __global__ __launch_bounds__(256) void conv_mfma4r(ConvParams p, Tile4 t) {
     const int n0 = ib * t.NB, oh0 = rb * t.TH, ih0 = oh0 * S - p.pad;
     const int ppi = t.TH * p.Wout, tot = t.NB * ppi;
 
-    // ---- filter bank -> registers: a[k][mt] = W[j*KPG + 4*mt + lane%4][k] -----
+    // ---- filter bank: global -> LDS, transposed to [filter%4][k][mt] ----------
+    // One 16-byte unit of the direct section is W[k][4*mt .. 4*mt+3]; behind the
+    // barrier below lane l reads its K*MT operands a[k][mt] = W[j*KPG + 4*mt + l%4][k]
+    // as one contiguous run.  (One dword load per operand and lane would keep the
+    // CU's vector memory path busy for longer than the whole convolution.)
+    constexpr int K = CPG * TAPS, WROW = K * MT + 4;   // +4 floats: the four rows start in different banks
     const __amdgpu_buffer_rsrc_t rw = make_rsrc(p.wd, t.w_bytes);
-    const unsigned wv = (lane & 3) * 4;
-    const unsigned wbase = j * (CPG * TAPS) * p.KPGd * 4;
-    float a[CPG * TAPS][MT];
+    float *wl = xs + t.in_floats + 4;
+    {
+        const unsigned wbase = j * K * p.KPGd * 4;
+        for (int u = tid; u < K * MT; u += NT) {
+            const int k = u / MT, mt = u - k * MT;
+            const f32x4 v = __builtin_bit_cast(
+                f32x4, __builtin_amdgcn_raw_buffer_load_b128(rw, (k * p.KPGd + mt * 4) * 4, wbase, 0));
 #pragma unroll
-    for (int k = 0; k < CPG * TAPS; ++k)
-#pragma unroll
-        for (int mt = 0; mt < MT; ++mt)
-            a[k][mt] = __uint_as_float(
-                __builtin_amdgcn_raw_buffer_load_b32(rw, wv, wbase + (k * p.KPGd + mt * 4) * 4, 0));
+            for (int f = 0; f < 4; ++f) wl[f * WROW + k * MT + mt] = v[f];
+        }
+    }
 
     // ---- stage the group's input slab with a zero halo -----------------------
     const __amdgpu_buffer_rsrc_t rx = make_rsrc(p.x, t.x_bytes);
@@ -125,6 +133,15 @@ __global__ __launch_bounds__(256) void conv_mfma4r(ConvParams p, Tile4 t) {
 
     __syncthreads();
 
+    float a[K][MT];
+    {
+        const float *wr = wl + (lane & 3) * WROW;
+#pragma unroll
+        for (int k = 0; k < K; ++k)
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) a[k][mt] = wr[k * MT + mt];
+    }
+
 #pragma unroll
     for (int c = 0; c < CPG; ++c) {
 #pragma unroll
@@ -148,15 +165,24 @@ __global__ __launch_bounds__(256) void conv_mfma4r(ConvParams p, Tile4 t) {
     // ---- epilogue: register r of (nt, mt) is filter 4*mt + r at this lane's pixel
     const __amdgpu_buffer_rsrc_t ry = make_rsrc(p.y, t.y_bytes);
     if (p.res) {
+        // all residual loads in flight before the first one is consumed
         const __amdgpu_buffer_rsrc_t rr = make_rsrc(p.res, t.y_bytes);
+        float rv[NTILE][MT][4];
 #pragma unroll
         for (int nt = 0; nt < NTILE; ++nt)
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
                 for (int r = 0; r < 4; ++r)
-                    acc[nt][mt][r] +=
+                    rv[nt][mt][r] =
                         __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rr, ooff[nt], (mt * 4 + r) * HWo * 4, 0));
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int nt = 0; nt < NTILE; ++nt)
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) acc[nt][mt][r] += rv[nt][mt][r];
     }
 #pragma unroll
     for (int nt = 0; nt < NTILE; ++nt)
@@ -212,7 +238,7 @@ bool plan4_tile(const ConvParams &p, const PackGeom &g, int NTILE, Tile4 *out) {
     // Row pitch: smallest conflict count within the LDS budget.
     int best_lw = 0, best_cost = 1 << 30;
     for (int lw = lw0; lw < lw0 + 32; lw += t.vec ? 4 : 1) {
-        const size_t bytes = ((size_t)round_up(g.CPG * t.NB * t.IHt * lw, 4) + 4) * sizeof(float);
+        const size_t bytes = ((size_t)round_up(g.CPG * t.NB * t.IHt * lw, 4) + 4 + 4 * (g.Kred * (g.KPG / 4) + 4)) * sizeof(float);
         if (bytes > (size_t)kLdsBudget4) break;
         const int cost = bank_cost4(p, t, lw);
         if (cost < best_cost) {
@@ -255,7 +281,7 @@ bool plan4_tile(const ConvParams &p, const PackGeom &g, int NTILE, Tile4 *out) {
 
 template <int CPG, int MT, int NTILE, int S, typename TIN>
 hipError_t launch4_inst(const ConvParams &p, const Tile4 &t, hipStream_t s) {
-    const size_t lds = ((size_t)t.in_floats + 4) * sizeof(float);
+    const size_t lds = ((size_t)t.in_floats + 4 + 4 * (CPG * 9 * MT + 4)) * sizeof(float);   // tile, spare slot, filter bank
     dim3 grid(t.row_blocks * t.img_blocks, p.groups);
     hipLaunchKernelGGL((conv_mfma4r<CPG, MT, NTILE, S, TIN>), grid, dim3(256), lds, s, p, t);
     return hipGetLastError();

@@ -387,7 +387,7 @@ int bank_cost_w(const ConvParams &p, const Tile16w &t, int plane) {
 
 bool planW_cfg(const ConvParams &p, const PackGeom &g, const CfgW &c, int ckb, Tile16w *out) {
     const int MB = 16 * c.MI, PW = 16 * c.NI, CK = 4 * ckb;
-    if (g.KPG % MB || g.CPG % CK) return false;
+    if ((g.mtiles * 16) % MB || g.CPG % CK) return false;
     Tile16w t{};
     if (!split_pixels(p, PW, &t.NB, &t.TH)) return false;
     t.IHt = (t.TH - 1) * p.stride + 3;
@@ -425,7 +425,7 @@ bool planW_cfg(const ConvParams &p, const PackGeom &g, const CfgW &c, int ckb, T
     if (lds > kLdsMaxW) return false;
     t.row_blocks = (p.Hout + t.TH - 1) / t.TH;
     t.img_blocks = (p.N + t.NB - 1) / t.NB;
-    t.oc_blocks = g.KPG / MB;
+    t.oc_blocks = g.mtiles * 16 / MB;
     const long wt = (long)t.row_blocks * t.img_blocks;
     if (wt > 1000000000L || p.groups * t.oc_blocks > 65535) return false;
     t.wave_tiles = (int)wt;

@@ -50,12 +50,12 @@ __global__ void pack_mfma_kernel(const float *__restrict__ w, float *__restrict_
     const int j = (int)(r / a.ksteps);
     const int taps = a.KH * a.KW;
     const int cblk = ks / taps, tap = ks % taps;
-    const int oc_in = lane % a.variant;
-    const int sub = lane / a.variant;
+    const int oc_in = lane % 16;
+    const int sub = lane / 16;
     const int c = cblk * a.ksub + sub;
     float v = 0.f;
-    if (c < a.CPG) {
-        const int oc = j * a.KPG + mt * a.variant + oc_in;
+    if (c < a.CPG && mt * 16 + oc_in < a.KPG) {
+        const int oc = j * a.KPG + mt * 16 + oc_in;
         v = w[(size_t)oc * a.Kred + (size_t)c * taps + tap];
         if (a.to_bf16) v = round_bf16(v);
     }
@@ -102,9 +102,9 @@ __global__ void unpack_kernel(const float *__restrict__ sec, float *__restrict__
     }
     const int taps = a.KH * a.KW;
     const int c = k / taps, tap = k % taps;
-    const int mt = o / a.variant, oc_in = o % a.variant;
+    const int mt = o / 16, oc_in = o % 16;
     const int cblk = c / a.ksub, sub = c % a.ksub;
-    const int lane = sub * a.variant + oc_in;
+    const int lane = sub * 16 + oc_in;
     const int ks = cblk * taps + tap;
     w[d] = sec[(((size_t)j * a.ksteps + ks) * a.mtiles + mt) * 64 + lane];
 }
