@@ -52,7 +52,7 @@ def main():
     ap.add_argument("--traffic-probe", action="store_true",
                     help="first run a plain 256 MiB device copy three times: the known-size kernel "
                          "against which rocprofv3's FETCH_SIZE / WRITE_SIZE counters are scaled")
-    ap.add_argument("--sweep", choices=["wrn", "resnet_bf16", "depthwise", "latency"],
+    ap.add_argument("--sweep", choices=["wrn", "wrn_n256", "resnet_bf16", "depthwise", "latency"],
                     help="instead of the headline step, time every layer of a configuration family "
                          "and print one JSON line with a row per layer")
     ap.add_argument("--fusion", action="store_true",
@@ -88,6 +88,10 @@ def main():
         if args.sweep == "wrn":
             shapes = [s for g in GROUPS for s in wl.wrn_grouped_shapes(BATCH, g)]
             rows = layer_timing.time_layers(shapes, "f32")
+        elif args.sweep == "wrn_n256":
+            # the compute-bound layers again at batch 256: steady-state matrix-core efficiency
+            shapes = [s for g in (1, 2, 4) for s in wl.wrn_grouped_shapes(256, g) if s.stride == 1]
+            rows = layer_timing.time_layers(shapes, "f32", inner=4, reps=5)
         elif args.sweep == "latency":
             # whole-network latency at batch 1 (recorded chains replayed back to back)
             rows = []

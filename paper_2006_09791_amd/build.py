@@ -12,7 +12,7 @@ LIB = os.path.join(HERE, "libgspc.so")
 
 SOURCES = ["gspc_api.cpp", "pack_kernels.hip", "chain_kernels.hip",
            "direct_kernels.hip", "mfma_kernels.hip", "mfma4_kernels.hip", "mfmab_kernels.hip",
-           "mfmaw_kernels.hip", "fused_kernels.hip"]
+           "mfmaw_kernels.hip", "fused_kernels.hip", "dw_kernels.hip"]
 
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-x", "hip",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
@@ -20,8 +20,6 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-x", "hip",
          "-I", os.path.join(ROOT, "include"), "-I", CSRC]
 if os.environ.get("GSPC_PHASE_TIMING"):      # developer aid: per-phase timestamps
     FLAGS.append("-DGSPC_PHASE_TIMING")
-if os.environ.get("GSPC_EXP"):               # developer aid: ablation variants (wrong results)
-    FLAGS.append("-DGSPC_EXP=" + os.environ["GSPC_EXP"])
 
 
 def _hipcc():

@@ -351,6 +351,8 @@ hipError_t launch_direct(const ConvParams &p, hipStream_t s, const char **name) 
                             (p.in_bf16 ? ",bf16>" : ",f32>"));
         return p.in_bf16 ? launch_small<uint16_t>(p, ts, s) : launch_small<float>(p, ts, s);
     }
+    DwPlan dw;
+    if (plan_dw_planes(p, &dw)) return launch_dw_planes(p, dw, s, name);
     TileF tf;
     if (plan_flat(p, &tf)) {
         *name = intern_name("conv_direct_flat<" + std::to_string(p.KPG) + (p.in_bf16 ? ",bf16>" : ",f32>"));

@@ -16,10 +16,6 @@
 
 #include "conv_common.h"
 
-#ifndef GSPC_EXP
-#define GSPC_EXP 0
-#endif
-
 namespace gspc {
 
 constexpr int kFuseMaxUnits = 32 * 9 * 32 / 4;   // 16-byte units of the largest layer's weights (CPG = 32)
@@ -142,7 +138,7 @@ __global__ __launch_bounds__(64 * NW) void conv_fused_run(FusedRun r) {
             f32x4 acc[NI];
 #pragma unroll
             for (int ni = 0; ni < NI; ++ni) acc[ni] = f32x4{0.f, 0.f, 0.f, 0.f};
-            for (int cb = 0; cb < (GSPC_EXP == 11 ? 0 : cblocks); ++cb) {
+            for (int cb = 0; cb < cblocks; ++cb) {
                 const int c = cb * 4 + lk;
                 const bool avalid = fvalid && c < r.CPG;
                 const int cc = c < r.CPG ? c : r.CPG - 1;

@@ -109,6 +109,13 @@ struct Mfma4Plan {
 bool plan_mfma4(const ConvParams &p, const PackGeom &g, Mfma4Plan *out);
 hipError_t launch_mfma4(const ConvParams &p, const Mfma4Plan &plan, hipStream_t s, const char **name);
 
+// Depthwise 3x3 on whole small planes (dw_kernels.hip); plan is opaque to the caller.
+struct DwPlan {
+    int data[24];
+};
+bool plan_dw_planes(const ConvParams &p, DwPlan *out);
+hipError_t launch_dw_planes(const ConvParams &p, const DwPlan &plan, hipStream_t s, const char **name);
+
 // Fused run of consecutive grouped 3x3 layers (fused_kernels.hip).
 constexpr int kFuseMaxLayers = 16, kFuseMaxTiles = 3, kFuseMaxInputs = 3;
 struct FusedLayer {

@@ -23,10 +23,6 @@
 
 #include "conv_common.h"
 
-#ifndef GSPC_EXP
-#define GSPC_EXP 0
-#endif
-
 namespace gspc {
 
 constexpr int kTmaxW = 4;    // input staging slots (16 bytes per lane each) per chunk
@@ -96,7 +92,7 @@ __global__ __launch_bounds__(256) void conv_mfma16w(ConvParams p, Tile16w t) {
         for (int k = 0; k < WMAX; ++k)
             if (k >= lo && k < hi)
                 pw[k] = __builtin_bit_cast(
-                    f32x4, __builtin_amdgcn_raw_buffer_load_b128(rw, k < (GSPC_EXP == 3 ? W0 : t.wslots) ? wvoff : kOob,
+                    f32x4, __builtin_amdgcn_raw_buffer_load_b128(rw, k < t.wslots ? wvoff : kOob,
                                                                  wblk + k * kStepsPerSlot * wrow, 0));
     };
     auto commit_w = [&](int lo, int hi) __attribute__((always_inline)) {
@@ -129,11 +125,7 @@ __global__ __launch_bounds__(256) void conv_mfma16w(ConvParams p, Tile16w t) {
     f32x4 pin0[TMAX], pin1[TMAX];
     auto fetch_x = [&](int chunk, f32x4 (&pin)[TMAX]) __attribute__((always_inline)) {
         const unsigned so = chunk * CK * HW * ES;
-#if GSPC_EXP == 1
-        const bool on = chunk < 2;
-#else
         const bool on = chunk < t.nchunks;
-#endif
 #pragma unroll
         for (int k = 0; k < TMAX; ++k) pin[k] = buf_load_in<TIN>(rx, on ? xoff[k] : kOob, so, 1);
     };
@@ -148,9 +140,6 @@ __global__ __launch_bounds__(256) void conv_mfma16w(ConvParams p, Tile16w t) {
     fetch_w(0, W0);
     fetch_x(0, pin0);
     fetch_x(1, pin1);
-#if GSPC_EXP == 4
-    fetch_w(W0, WMAX);
-#endif
     GSPC_STAMPW(1)
 
     // ---- per-lane pixel coordinates ----------------------------------------
@@ -202,9 +191,6 @@ __global__ __launch_bounds__(256) void conv_mfma16w(ConvParams p, Tile16w t) {
         const float *ws = smem + (ch * KCHUNK + row * 3) * (MI * 64) + lane;
 #pragma unroll
         for (int kw = 0; kw < 3; ++kw) {
-#if GSPC_EXP == 2
-            if (ch > 1) continue;
-#endif
 #pragma unroll
             for (int mi = 0; mi < MI; ++mi) a[kw][mi] = ws[(kw * MI + mi) * 64];
 #pragma unroll
@@ -242,9 +228,7 @@ __global__ __launch_bounds__(256) void conv_mfma16w(ConvParams p, Tile16w t) {
             __builtin_amdgcn_sched_barrier(0);   // operand reads first, then the MFMAs they overlap with
 #pragma unroll
             for (int kw = 0; kw < 3; ++kw) {
-#if GSPC_EXP != 4
                 fetch_w(W0 + (i * 3 + kw) * PER, W0 + (i * 3 + kw + 1) * PER);
-#endif
 #pragma unroll
                 for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
@@ -506,6 +490,9 @@ bool plan_mfma16w(const ConvParams &p, const PackGeom &g, Mfma16wPlan *out) {
         }
     }
     if (best < 0) return false;
+    // Very large batches: blocks would queue up behind each other, each copying its filter tile again;
+    // the shared-tile kernel with its larger blocks is faster there.
+    if ((long)bt.wave_tiles * bt.oc_blocks * p.groups > 16384) return false;
     out->inst = best;
     out->ckb = ckb;
     static_assert(sizeof(Tile16w) <= sizeof(out->data), "plan storage too small");

@@ -77,6 +77,9 @@ SWEEP = [
     S(1, 8, 12, 12, 8, 3, 3, 1, 1, 8),     # depthwise
     S(2, 8, 7, 7, 8, 3, 3, 2, 1, 8),       # depthwise stride 2, odd size
     S(1, 8, 9, 9, 16, 3, 3, 1, 1, 8),      # depthwise, channel multiplier 2
+    S(3, 37, 14, 14, 37, 3, 3, 1, 1, 37),  # depthwise on whole small planes, plane count not a multiple of 4
+    S(5, 13, 7, 7, 13, 3, 3, 2, 1, 13),    # the same, stride 2, odd plane size (tail of the last block)
+    S(2, 6, 28, 28, 6, 3, 3, 2, 1, 6),     # 28x28 stride 2
     S(1, 10, 9, 8, 15, 2, 3, 1, 0, 5),     # KH != KW, no padding
     S(1, 4, 6, 6, 4, 5, 5, 1, 2, 2),       # 5x5
     S(1, 8, 5, 5, 8, 3, 3, 3, 2, 2),       # stride 3, pad 2
