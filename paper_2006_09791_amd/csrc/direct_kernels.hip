@@ -344,6 +344,9 @@ hipError_t launch_small(const ConvParams &p, const TileS &t, hipStream_t s) {
 
 hipError_t launch_direct(const ConvParams &p, hipStream_t s, const char **name) {
     static const bool no_small = std::getenv("GSPC_NO_SMALL") != nullptr;   // tuning aid
+    // depthwise planes small enough to sit whole in LDS (up to about 40x40)
+    DwPlan dw;
+    if (plan_dw_planes(p, &dw)) return launch_dw_planes(p, dw, s, name);
     TileS ts;
     if (!no_small && plan_small(p, &ts)) {
         *name = intern_name("conv_direct_small<" + std::to_string(p.CPG) + "," + std::to_string(p.KPG) + "," +
@@ -351,8 +354,6 @@ hipError_t launch_direct(const ConvParams &p, hipStream_t s, const char **name) 
                             (p.in_bf16 ? ",bf16>" : ",f32>"));
         return p.in_bf16 ? launch_small<uint16_t>(p, ts, s) : launch_small<float>(p, ts, s);
     }
-    DwPlan dw;
-    if (plan_dw_planes(p, &dw)) return launch_dw_planes(p, dw, s, name);
     TileF tf;
     if (plan_flat(p, &tf)) {
         *name = intern_name("conv_direct_flat<" + std::to_string(p.KPG) + (p.in_bf16 ? ",bf16>" : ",f32>"));
