@@ -91,6 +91,7 @@ def main():
         elif args.sweep == "wrn_n256":
             # the compute-bound layers again at batch 256: steady-state matrix-core efficiency
             shapes = [s for g in (1, 2, 4) for s in wl.wrn_grouped_shapes(256, g) if s.stride == 1]
+            shapes += [s for s in wl.wrn_grouped_shapes(1024, 1) if s.stride == 1]
             rows = layer_timing.time_layers(shapes, "f32", inner=4, reps=5)
         elif args.sweep == "latency":
             # whole-network latency at batch 1 (recorded chains replayed back to back)

@@ -32,7 +32,7 @@ struct Tile16w {
     int NB, TH, IHt;         // images, output rows per wave tile; staged input rows
     int LW, IMG, PLANE, XO;  // LDS row pitch, floats per image / per channel, column of input col 0
     int nchunks;             // chunks of 4*CKB channels
-    int row_blocks, img_blocks, oc_blocks, wave_tiles;
+    int row_blocks, img_blocks, oc_blocks, wave_tiles, tile_groups;   // tile_groups = ceil(wave_tiles / 4)
     int tpr_log2;            // lanes per staged row (log2), 16 bytes per lane
     int tasks, xslots;       // staged rows per chunk, rows per lane per chunk
     int wslots;              // weight slots in total (the first chunk's count is static)
@@ -53,7 +53,7 @@ __device__ unsigned long long g_phase_w[8 * 4096];
 #define GSPC_STAMPW(i)
 #endif
 
-template <int MI, int NI, int S, int CKB, typename TIN>
+template <int MI, int NI, int S, int CKB, bool PERSIST, typename TIN>
 __global__ __launch_bounds__(256) void conv_mfma16w(ConvParams p, Tile16w t) {
     GSPC_STAMPW(0)
     constexpr int NT = 256, TAPS = 9, CK = 4 * CKB, KCHUNK = CKB * TAPS, ES = (int)sizeof(TIN);
@@ -66,13 +66,8 @@ __global__ __launch_bounds__(256) void conv_mfma16w(ConvParams p, Tile16w t) {
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const unsigned j = fast_div(blockIdx.y, t.m_ocb);
     const int ob = blockIdx.y - j * t.oc_blocks;
-    const int wt = blockIdx.x * 4 + wave;      // this wave's pixel tile
-    const bool live = wt < t.wave_tiles;       // a dead wave loads zeros and stores nothing
-    const unsigned ib = fast_div(live ? wt : 0, t.m_rowb);
-    const int rb = (live ? wt : 0) - ib * t.row_blocks;
-    const int n0 = ib * t.NB, oh0 = rb * t.TH, ih0 = oh0 * S - p.pad;
     const int ppi = t.TH * p.Wout, tot = t.NB * ppi;
-    const unsigned HW = p.H * p.W;
+    const unsigned HW = p.H * p.W, HWo = p.Hout * p.Wout;
 
     const __amdgpu_buffer_rsrc_t rx = make_rsrc(p.x, t.x_bytes);
     const __amdgpu_buffer_rsrc_t rw = make_rsrc(p.wm, t.w_bytes);
@@ -101,27 +96,67 @@ __global__ __launch_bounds__(256) void conv_mfma16w(ConvParams p, Tile16w t) {
             if (k >= lo && k < hi) smem4[k * NT + tid] = pw[k];
     };
 
+    fetch_w(0, W0);   // first chunk's weights: nothing else is needed to ask for them
+
     // ---- private input ring: wave w owns two stages -------------------------
     // (a stage ends with a 16-byte spare slot that absorbs the writes of idle lanes)
     float *ring = smem + t.w_floats + wave * (2 * t.stage_floats);
     const unsigned spare = (t.stage_floats - 4) * 4;   // byte offset of the spare slot in a stage
     const int rpp = 64 >> t.tpr_log2;
     const int row0 = lane >> t.tpr_log2, colv = lane & ((1 << t.tpr_log2) - 1);
-    unsigned xoff[TMAX], xlds[TMAX];
+    // What depends on the lane alone: where a staged row goes in the ring, its
+    // offset from the tile's first input element, and where the lane's pixels sit.
+    unsigned xlds[TMAX];
+    int xrow[TMAX], ximg[TMAX], xlane[TMAX];   // staged row k of this lane: row and image inside the tile, byte offset
 #pragma unroll
     for (int k = 0; k < TMAX; ++k) {
         const int task = row0 + k * rpp;
-        xoff[k] = kOob;
         xlds[k] = spare;
+        xrow[k] = -(1 << 20);   // never in range
+        ximg[k] = 0;
+        xlane[k] = 0;
         if (k < t.xslots && task < t.tasks && colv * 4 < p.W) {
             const int cimg = fast_div(task, t.m_IHt), r = task - cimg * t.IHt;
             const int c = fast_div(cimg, t.m_NB), img = cimg - c * t.NB;
-            const int ih = ih0 + r, n = n0 + img;
             xlds[k] = (c * t.PLANE + img * t.IMG + r * t.LW + t.XO + colv * 4) * 4;
-            if (live && n < p.N && ih >= 0 && ih < p.H)
-                xoff[k] = (((n * p.Cin + j * p.CPG + c) * p.H + ih) * p.W + colv * 4) * ES;
+            xrow[k] = r;
+            ximg[k] = img;
+            xlane[k] = (((img * p.Cin + c) * p.H + r) * p.W + colv * 4) * ES;
         }
     }
+    int base[NI], pimg[NI], prow[NI], olane[NI];
+#pragma unroll
+    for (int ni = 0; ni < NI; ++ni) {
+        const int q = ni * 16 + (lane & 15);
+        const int qq = q < tot ? q : 0;
+        const int img = fast_div(qq, t.m_ppi), rem = qq - img * ppi;
+        const int r = fast_div(rem, t.m_Wout), col = rem - r * p.Wout;
+        base[ni] = (lane >> 4) * t.PLANE + img * t.IMG + r * S * t.LW + (t.XO - p.pad) + col * S;
+        pimg[ni] = img;
+        prow[ni] = q < tot ? r : 1 << 20;   // rows of idle lanes are never in range
+        olane[ni] = ((img * p.Cout + 4 * (lane >> 4)) * HWo + r * p.Wout + col) * 4;
+    }
+    // What depends on the pixel tile: global offsets of the staged rows and of
+    // the outputs (kOob = no access).  A wave past the last tile loads zeros and
+    // stores nothing.
+    unsigned xoff[TMAX], ooff[NI];
+    auto set_tile = [&](int tile_group) __attribute__((always_inline)) {
+        const int wt = tile_group * 4 + wave;
+        const bool live = wt < t.wave_tiles;
+        const unsigned ib = fast_div(live ? wt : 0, t.m_rowb);
+        const int rb = (live ? wt : 0) - ib * t.row_blocks;
+        const int n0 = ib * t.NB, oh0 = rb * t.TH, ih0 = oh0 * S - p.pad;
+        const int nleft = live ? p.N - n0 : 0;   // images of this tile that exist
+        const int xtile = (((n0 * p.Cin + j * p.CPG) * p.H + ih0) * p.W) * ES;
+        const int otile = ((n0 * p.Cout + j * p.KPG) * HWo + oh0 * p.Wout) * 4;
+#pragma unroll
+        for (int k = 0; k < TMAX; ++k)
+            xoff[k] = (ximg[k] < nleft && xrow[k] >= -ih0 && xrow[k] < p.H - ih0) ? (unsigned)(xtile + xlane[k]) : kOob;
+#pragma unroll
+        for (int ni = 0; ni < NI; ++ni)
+            ooff[ni] = (pimg[ni] < nleft && prow[ni] < p.Hout - oh0) ? (unsigned)(otile + olane[ni]) : kOob;
+    };
+    set_tile(blockIdx.x);
     f32x4 pin0[TMAX], pin1[TMAX];
     auto fetch_x = [&](int chunk, f32x4 (&pin)[TMAX]) __attribute__((always_inline)) {
         const unsigned so = chunk * CK * HW * ES;
@@ -136,28 +171,10 @@ __global__ __launch_bounds__(256) void conv_mfma16w(ConvParams p, Tile16w t) {
             if (k < t.xslots) *reinterpret_cast<f32x4 *>(bb + xlds[k]) = pin[k];
     };
 
-    // First chunk's weights and input, then the second chunk's input.
-    fetch_w(0, W0);
+    // First and second chunk's input of the first tile (the first chunk's weights are on their way).
     fetch_x(0, pin0);
     fetch_x(1, pin1);
     GSPC_STAMPW(1)
-
-    // ---- per-lane pixel coordinates ----------------------------------------
-    int base[NI];
-    unsigned ooff[NI];   // byte offset of this lane's first output element, or kOob
-    const unsigned HWo = p.Hout * p.Wout;
-#pragma unroll
-    for (int ni = 0; ni < NI; ++ni) {
-        const int q = ni * 16 + (lane & 15);
-        const int qq = q < tot ? q : 0;
-        const int img = fast_div(qq, t.m_ppi), rem = qq - img * ppi;
-        const int r = fast_div(rem, t.m_Wout), col = rem - r * p.Wout;
-        base[ni] = (lane >> 4) * t.PLANE + img * t.IMG + r * S * t.LW + (t.XO - p.pad) + col * S;
-        const int n = n0 + img, oh = oh0 + r;
-        ooff[ni] = (live && q < tot && n < p.N && oh < p.Hout)
-                       ? (((unsigned)n * p.Cout + j * p.KPG + 4 * (lane >> 4)) * HWo + oh * p.Wout + col) * 4
-                       : kOob;
-    }
 
     f32x4 acc[MI][NI];
 #pragma unroll
@@ -260,6 +277,7 @@ __global__ __launch_bounds__(256) void conv_mfma16w(ConvParams p, Tile16w t) {
     // ch&1; before its last row chunk ch+1 moves registers -> the other stage,
     // chunk ch+2 is requested from global memory at its start (two register
     // sets pin0 / pin1).
+    auto steady = [&]() __attribute__((always_inline)) {
     for (int ch = 1; ch < t.nchunks; ch += 2) {
         // odd chunk: pin1 is free (chunk ch is in LDS), pin0 holds chunk ch+1
         fetch_x(ch + 2, pin1);
@@ -292,19 +310,13 @@ __global__ __launch_bounds__(256) void conv_mfma16w(ConvParams p, Tile16w t) {
             }
         }
     }
-
-    GSPC_STAMPW(5)
-#ifdef GSPC_PHASE_TIMING
-    if (threadIdx.x == 0) {
-        const unsigned bid = blockIdx.x + blockIdx.y * gridDim.x;
-        if (bid < 4096) g_phase_w[bid * 8 + 7] = ((__builtin_amdgcn_s_memtime() - clk0) & 0xffffffffull) | (clkc1 << 32);
-    }
-#endif
+    };
     // ---- epilogue: optional residual and ReLU, NCHW store -------------------
     // Register r of tile (mi, ni) is filter 16*(tile row) + 4*(lane/16) + r at
     // this lane's pixel; the 4*(lane/16) part already sits in ooff.
     const __amdgpu_buffer_rsrc_t ry = make_rsrc(p.y, t.y_bytes);
     const unsigned oc0 = ob * MI * 16;
+    auto epilogue = [&](const unsigned (&ooff)[NI]) __attribute__((always_inline)) {
     if (p.res) {
         const __amdgpu_buffer_rsrc_t rr = make_rsrc(p.res, t.y_bytes);
 #pragma unroll
@@ -327,6 +339,59 @@ __global__ __launch_bounds__(256) void conv_mfma16w(ConvParams p, Tile16w t) {
                 __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(v), ry, ooff[ni],
                                                       (oc0 + mi * 16 + r) * HWo * 4, 0);
             }
+    };
+
+    steady();
+    GSPC_STAMPW(5)
+#ifdef GSPC_PHASE_TIMING
+    if (threadIdx.x == 0) {
+        const unsigned bid = blockIdx.x + blockIdx.y * gridDim.x;
+        if (bid < 4096) g_phase_w[bid * 8 + 7] = ((__builtin_amdgcn_s_memtime() - clk0) & 0xffffffffull) | (clkc1 << 32);
+    }
+#endif
+
+    // ---- further pixel tiles of this block (large batches): the filters stay ----
+    // The next tile's first two chunks are requested before the results of the
+    // current one are stored, so their latency hides behind the epilogue.
+    if (!PERSIST) {   // one tile group per block: the common, latency-bound case, kept lean
+        epilogue(ooff);
+        return;
+    }
+    for (int tg = blockIdx.x;;) {
+        const int next = tg + gridDim.x;
+        unsigned ooff_done[NI];
+#pragma unroll
+        for (int ni = 0; ni < NI; ++ni) ooff_done[ni] = ooff[ni];
+        const bool more = next < t.tile_groups;
+        if (more) {
+            set_tile(next);
+            fetch_x(0, pin0);
+            fetch_x(1, pin1);
+        }
+        epilogue(ooff_done);
+        if (!more) break;
+        tg = next;
+#pragma unroll
+        for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+            for (int ni = 0; ni < NI; ++ni) acc[mi][ni] = f32x4{0.f, 0.f, 0.f, 0.f};
+        commit_x(0, pin0);
+        fetch_x(2, pin0);
+        load_row(0, 0, opa[0], opb[0]);
+#pragma unroll
+        for (int i = 0; i < R; ++i) {
+            if (i + 1 < R) {
+                load_row(0, i + 1, opa[(i + 1) & 1], opb[(i + 1) & 1]);
+            } else {
+                if (t.nchunks > 1) commit_x(1, pin1);
+                load_row(1, 0, opa[(i + 1) & 1], opb[(i + 1) & 1]);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            mfma_row(opa[i & 1], opb[i & 1]);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        steady();
+    }
     GSPC_STAMPW(6)
 }
 
@@ -413,6 +478,7 @@ bool planW_cfg(const ConvParams &p, const PackGeom &g, const CfgW &c, int ckb, T
     const long wt = (long)t.row_blocks * t.img_blocks;
     if (wt > 1000000000L || p.groups * t.oc_blocks > 65535) return false;
     t.wave_tiles = (int)wt;
+    t.tile_groups = (t.wave_tiles + 3) / 4;
     t.m_IHt = div_magic(t.IHt);
     t.m_NB = div_magic(t.NB);
     t.m_ppi = div_magic(t.TH * p.Wout);
@@ -440,15 +506,27 @@ size_t lds_bytes_w(const Tile16w &t) {
 template <int MI, int NI, int S, int CKB>
 hipError_t launchW_inst(const ConvParams &p, const Tile16w &t, hipStream_t s) {
     const size_t lds = lds_bytes_w(t);
-    dim3 grid((t.wave_tiles + 3) / 4, p.groups * t.oc_blocks);
-    auto kern = conv_mfma16w<MI, NI, S, CKB, float>;
+    // One block per group of four wave tiles while the chip can hold them all at once; beyond that
+    // every block walks over several tile groups, keeping its filters.
+    const long gy = (long)p.groups * t.oc_blocks;
+    long per_cu = (long)(kLdsMaxW / lds);
+    per_cu = per_cu < 1 ? 1 : per_cu > 4 ? 4 : per_cu;
+    const long cap = kNumCU * per_cu, total = (long)t.tile_groups * gy;
+    long gx = t.tile_groups;
+    if (total > cap) {
+        const long rounds = (total + cap - 1) / cap;
+        gx = (t.tile_groups + rounds - 1) / rounds;
+    }
+    dim3 grid((unsigned)gx, (unsigned)gy);
+    const bool persist = gx < t.tile_groups;
+    auto kern = persist ? conv_mfma16w<MI, NI, S, CKB, true, float> : conv_mfma16w<MI, NI, S, CKB, false, float>;
     if (lds > 64 * 1024) {
-        static thread_local bool raised = false;   // per instantiation and thread
-        if (!raised) {
+        static thread_local bool raised[2] = {false, false};   // per instantiation and thread
+        if (!raised[persist]) {
             hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsMaxW);
             if (e != hipSuccess) return e;
-            raised = true;
+            raised[persist] = true;
         }
     }
     hipLaunchKernelGGL(kern, grid, dim3(256), lds, s, p, t);
@@ -490,9 +568,6 @@ bool plan_mfma16w(const ConvParams &p, const PackGeom &g, Mfma16wPlan *out) {
         }
     }
     if (best < 0) return false;
-    // Very large batches: blocks would queue up behind each other, each copying its filter tile again;
-    // the shared-tile kernel with its larger blocks is faster there.
-    if ((long)bt.wave_tiles * bt.oc_blocks * p.groups > 16384) return false;
     out->inst = best;
     out->ckb = ckb;
     static_assert(sizeof(Tile16w) <= sizeof(out->data), "plan storage too small");
