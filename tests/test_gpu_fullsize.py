@@ -29,7 +29,7 @@ def _sampled_check(s, seed, dtype_bf16, n_img, n_oc, tol_same, tol_unrounded=Non
     name = b.gspc_last_kernel()
     torch.cuda.synchronize()
     rng = np.random.default_rng(seed + 1)
-    imgs = np.sort(rng.choice(s.N, size=min(n_img, s.N), replace=False))
+    imgs = np.unique(np.concatenate([[0, s.N - 1], rng.choice(s.N, size=min(n_img, s.N), replace=False)]))
     # sampled filters: first, last, and random ones (hits several groups and tile positions)
     ocs = np.unique(np.concatenate([[0, s.Cout - 1], rng.choice(s.Cout, size=n_oc, replace=False)]))
     got = y[torch.from_numpy(imgs).to(dev)][:, torch.from_numpy(ocs).to(dev)].cpu().numpy()
@@ -53,6 +53,35 @@ def _sampled_check(s, seed, dtype_bf16, n_img, n_oc, tol_same, tol_unrounded=Non
 def test_wrn_layers_batch64_fp32(g):
     for i, s in enumerate(wl.wrn_grouped_shapes(64, g)):
         _sampled_check(s, wl.make_seed(2, 100 + i, g), False, n_img=3, n_oc=4, tol_same=TOL_F32)
+
+
+@pytest.mark.parametrize("g", [1, 2])
+def test_wrn_layers_batch256_fp32(g):
+    """More blocks than the chip holds at once: the resident-filter kernel walks
+    over several pixel tiles per block (first, last and random images sampled)."""
+    for i, s in enumerate(wl.wrn_grouped_shapes(256, g)):
+        name = _sampled_check(s, wl.make_seed(2, 300 + i, g), False, n_img=3, n_oc=4, tol_same=TOL_F32)
+        assert "conv_mfma16w" in name, name
+
+
+def test_residual_chain_batch256_fp32():
+    """Residual and ReLU epilogue of the multi-tile form, whole tensors."""
+    import torch
+    from helpers import gpu_chain, oracle_chain
+    from paper_2006_09791_amd import binding as b
+    N, C, hw = 256, 64, 16
+    ch = wl.Chain("big", (N, C, hw, hw))
+    ch.conv(0, 1, N, C, hw, hw, C, 3, 1, 1, 1, relu=True)
+    ch.conv(1, 2, N, C, hw, hw, C, 3, 1, 1, 1, relu=True, residual=0)
+    x0 = wl.make_input(ch.input_shape, 41)
+    weights = ch.make_weights(9)
+    lc, bufs = gpu_chain(ch, x0, weights)
+    b.gspc_run_layer_chain(lc)
+    torch.cuda.synchronize()
+    assert "conv_mfma16w" in b.gspc_last_kernel()
+    ref = oracle_chain(ch, x0, weights, threads=16)[2]
+    got = bufs[2][:ref.size].cpu().numpy().reshape(ref.shape)
+    assert rel_err(got, ref) < TOL_F32
 
 
 def test_wrn_stem_and_shortcuts_batch64_fp32():
