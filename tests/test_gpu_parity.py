@@ -70,6 +70,11 @@ SWEEP = [
     S(2, 32, 16, 16, 64, 3, 3, 2, 1, 2),   # KPG = 32, CPG = 16
     S(1, 64, 8, 8, 64, 3, 3, 1, 1, 1),     # KPG = 64
     S(3, 128, 8, 8, 128, 3, 3, 1, 1, 1),   # KPG = 128, odd batch vs images per block
+    S(3, 32, 12, 20, 48, 3, 3, 1, 1, 1),   # resident-filter kernel: rows wider than a 16-pixel run, ragged row blocks
+    S(5, 64, 10, 12, 64, 3, 3, 2, 1, 2),   # the same, stride 2, odd output plane (5x6)
+    S(2, 16, 6, 8, 16, 3, 3, 1, 0, 1),     # no padding
+    S(1, 32, 4, 4, 32, 3, 3, 1, 1, 1),     # several images per wave tile, fewer images than that
+    S(9, 32, 4, 4, 64, 3, 3, 1, 2, 2),     # pad 2, images per tile not dividing the batch
     S(1, 3, 32, 32, 32, 3, 3, 1, 1, 1),    # stem: CPG = 3 padded to the MFMA k extent
     S(1, 3, 40, 40, 64, 7, 7, 2, 3, 1),    # 7x7 stride 2
     S(2, 32, 32, 32, 64, 1, 1, 2, 0, 1),   # 1x1 stride 2 shortcut
