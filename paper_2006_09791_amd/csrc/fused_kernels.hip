@@ -381,9 +381,11 @@ int plan_fused_run(const gspc_layer_t *layers, int first, int count, void *const
     if (n < 2) return 0;
     const size_t lds = ((size_t)r.ntiles * r.TILE + 2 * (size_t)r.wfloats) * sizeof(float);
 
-    // Worth it?  A fused layer costs a block its MFMAs (32 cycles each, spread over four SIMDs) and a
-    // barrier; a separate launch costs about 5 us of launch and pipeline latency plus the layer at
-    // full-chip speed.
+    // Worth it?  Both sides are fits to measurements on this GPU (stage by stage, N = 1 and 64).  A
+    // fused layer costs a round of co-resident blocks about 2 us (barrier, epilogues, pipeline fill)
+    // plus 5.7 ns per MFMA of the blocks that share a CU (32 cycles each over four SIMDs, x 1.4); a
+    // separate launch costs about 4.2 us of launch and pipeline latency plus the layer at the speed of
+    // the kernel that would take it.
     {
         long per_cu = (long)(160 * 1024 / lds);
         per_cu = per_cu < 1 ? 1 : per_cu > 8 ? 8 : per_cu;
@@ -392,8 +394,10 @@ int plan_fused_run(const gspc_layer_t *layers, int first, int count, void *const
         long share = (blocks + kNumCU - 1) / kNumCU;   // blocks that share a CU at a time
         share = share > per_cu ? per_cu : share;
         const double mfmas = (double)((r.CPG + 15) / 16) * ((r.H * r.W + 15) / 16) * ((r.CPG + 3) / 4) * 9.0;
-        const double fused_us = (0.5 + share * mfmas * 32.0 / 4.0 / 2.0e3 * 1.3) * rounds;
-        const double unfused_us = 5.0 + (double)r.CPG * r.CPG * 9.0 * r.H * r.W * blocks / 30.0e6;
+        const double fused_us = (2.0 + 0.0057 * share * mfmas) * rounds;
+        const double macs = (double)r.CPG * r.CPG * 9.0 * r.H * r.W * blocks;
+        const double macs_per_us = r.W % 4 ? 20.0e6 : r.CPG >= 16 ? 45.0e6 : 25.0e6;
+        const double unfused_us = (r.CPG <= 2 ? 6.0 : 4.2) + macs / macs_per_us;   // CPG <= 2 runs on the plain-ALU kernel
         if (fused_us >= unfused_us) return 0;
     }
 
