@@ -499,6 +499,20 @@ bool planW_cfg(const ConvParams &p, const PackGeom &g, const CfgW &c, int ckb, T
     return true;
 }
 
+// One block per group of four wave tiles while the chip can hold them all at once; beyond that
+// every block walks over several tile groups, keeping its filters.
+long grid_x_w(const ConvParams &p, const Tile16w &t, size_t lds) {
+    const long gy = (long)p.groups * t.oc_blocks;
+    long per_cu = (long)(kLdsMaxW / lds);
+    per_cu = per_cu < 1 ? 1 : per_cu > 4 ? 4 : per_cu;
+    const long cap = kNumCU * per_cu, total = (long)t.tile_groups * gy;
+    if (total <= cap) return t.tile_groups;
+    const long rounds = (total + cap - 1) / cap;
+    return (t.tile_groups + rounds - 1) / rounds;
+}
+
+size_t lds_bytes_w(const Tile16w &t);
+
 size_t lds_bytes_w(const Tile16w &t) {
     return ((size_t)t.w_floats + 8 * (size_t)t.stage_floats) * sizeof(float);
 }
@@ -506,17 +520,7 @@ size_t lds_bytes_w(const Tile16w &t) {
 template <int MI, int NI, int S, int CKB>
 hipError_t launchW_inst(const ConvParams &p, const Tile16w &t, hipStream_t s) {
     const size_t lds = lds_bytes_w(t);
-    // One block per group of four wave tiles while the chip can hold them all at once; beyond that
-    // every block walks over several tile groups, keeping its filters.
-    const long gy = (long)p.groups * t.oc_blocks;
-    long per_cu = (long)(kLdsMaxW / lds);
-    per_cu = per_cu < 1 ? 1 : per_cu > 4 ? 4 : per_cu;
-    const long cap = kNumCU * per_cu, total = (long)t.tile_groups * gy;
-    long gx = t.tile_groups;
-    if (total > cap) {
-        const long rounds = (total + cap - 1) / cap;
-        gx = (t.tile_groups + rounds - 1) / rounds;
-    }
+    const long gx = grid_x_w(p, t, lds), gy = (long)p.groups * t.oc_blocks;
     dim3 grid((unsigned)gx, (unsigned)gy);
     const bool persist = gx < t.tile_groups;
     auto kern = persist ? conv_mfma16w<MI, NI, S, CKB, true, float> : conv_mfma16w<MI, NI, S, CKB, false, float>;
@@ -579,8 +583,10 @@ hipError_t launch_mfma16w(const ConvParams &p, const Mfma16wPlan &plan, hipStrea
     Tile16w t;
     std::memcpy(&t, plan.data, sizeof(t));
     const CfgW &c = kCfgW[plan.inst];
+    const bool persist = grid_x_w(p, t, lds_bytes_w(t)) < t.tile_groups;
     *name = intern_name("conv_mfma16w<" + std::to_string(c.MI) + "," + std::to_string(c.NI) + "," +
-                        std::to_string(p.stride) + "," + std::to_string(plan.ckb) + ",f32>");
+                        std::to_string(p.stride) + "," + std::to_string(plan.ckb) + "," +
+                        (persist ? "true" : "false") + ",f32>");
     switch (plan.inst) {
     case 0: return launchW_shape<2, 4>(p.stride, plan.ckb, p, t, s);
     case 1: return launchW_shape<2, 2>(p.stride, plan.ckb, p, t, s);

@@ -59,9 +59,11 @@ def test_wrn_layers_batch64_fp32(g):
 def test_wrn_layers_batch256_fp32(g):
     """More blocks than the chip holds at once: the resident-filter kernel walks
     over several pixel tiles per block (first, last and random images sampled)."""
+    names = []
     for i, s in enumerate(wl.wrn_grouped_shapes(256, g)):
-        name = _sampled_check(s, wl.make_seed(2, 300 + i, g), False, n_img=3, n_oc=4, tol_same=TOL_F32)
-        assert "conv_mfma16w" in name, name
+        names.append(_sampled_check(s, wl.make_seed(2, 300 + i, g), False, n_img=3, n_oc=4, tol_same=TOL_F32))
+        assert "conv_mfma16w" in names[-1], names[-1]
+    assert any(",true," in n for n in names), names   # the multi-tile instantiation ran
 
 
 def test_residual_chain_batch256_fp32():
@@ -78,7 +80,7 @@ def test_residual_chain_batch256_fp32():
     lc, bufs = gpu_chain(ch, x0, weights)
     b.gspc_run_layer_chain(lc)
     torch.cuda.synchronize()
-    assert "conv_mfma16w" in b.gspc_last_kernel()
+    assert "conv_mfma16w" in b.gspc_last_kernel() and ",true," in b.gspc_last_kernel()
     ref = oracle_chain(ch, x0, weights, threads=16)[2]
     got = bufs[2][:ref.size].cpu().numpy().reshape(ref.shape)
     assert rel_err(got, ref) < TOL_F32
