@@ -130,6 +130,8 @@ int gspc_pack_input_bf16(const void *in_dev, size_t count, void *out_dev);
  * of Algorithm 1, no kernel flip).
  *   input  : dev, [N][Cin][H][W], fp32 or bf16 as recorded in packed_weight
  *   output : dev, fp32 [N][Cout][Hout][Wout], fully overwritten
+ * Both pointers must be 16-byte aligned (GSPC_ERR_ARG otherwise): the kernels
+ * move 16 bytes per lane wherever the row width allows.
  * (Cin, Cout, KH, KW, groups) must equal those of the handle
  * (GSPC_ERR_MISMATCH otherwise).  Asynchronous on the selected stream. */
 int gspc_conv2d_grouped(const void *input, const gspc_packed_t *packed_weight,
@@ -186,7 +188,8 @@ int gspc_set_chain_fusion(int on);
 
 /* Runs the steps in order on the selected stream.  act_bufs[i] (dev) holds
  * act_bytes[i] bytes; every step is validated against those sizes before
- * anything is launched (GSPC_ERR_SPACE / GSPC_ERR_ARG).  A CONV whose handle
+ * anything is launched (GSPC_ERR_SPACE / GSPC_ERR_ARG); the buffers must be
+ * 16-byte aligned (GSPC_ERR_ARG).  A CONV whose handle
  * is GSPC_BF16 reads a bf16 src; every dst is fp32.  If per_layer_ms is not
  * NULL it receives n_layers elapsed times measured with HIP events, and the
  * call then waits for the stream to drain; otherwise it is asynchronous. */

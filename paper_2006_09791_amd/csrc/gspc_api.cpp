@@ -1,6 +1,7 @@
 // Host side of libgspc: argument validation, kernel-family dispatch and the
 // layer-chain runner.  All arithmetic happens in the HIP kernels.
 #include <cstdarg>
+#include <cstdint>
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
@@ -100,6 +101,8 @@ int prepare_conv(const void *input, const gspc_packed_t *pw, int N, int Cin, int
                  int W, int Cout, int KH, int KW, int stride, int pad, int groups,
                  void *output, gspc::ConvParams *p) {
     if (!input || !pw || !output) return fail(GSPC_ERR_NULL, "null pointer argument");
+    if ((reinterpret_cast<uintptr_t>(input) | reinterpret_cast<uintptr_t>(output)) & 15)
+        return fail(GSPC_ERR_ARG, "input and output must be 16-byte aligned");
     if (!valid_handle(pw)) return fail(GSPC_ERR_MISMATCH, "not a packed-weight handle of this library version");
     if (N <= 0 || H <= 0 || W <= 0 || stride <= 0 || pad < 0)
         return fail(GSPC_ERR_DIM, "non-positive dimension (N=%d H=%d W=%d stride=%d pad=%d)",
@@ -338,6 +341,9 @@ int gspc_run_layer_chain(const gspc_layer_t *layers, int n_layers, void *const *
     if (n_layers <= 0 || n_bufs <= 0) return fail(GSPC_ERR_ARG, "empty chain or buffer table");
     for (int b = 0; b < n_bufs; ++b)
         if (!act_bufs[b] && act_bytes[b]) return fail(GSPC_ERR_NULL, "activation buffer %d is null", b);
+    for (int b = 0; b < n_bufs; ++b)
+        if (reinterpret_cast<uintptr_t>(act_bufs[b]) & 15)
+            return fail(GSPC_ERR_ARG, "activation buffer %d is not 16-byte aligned", b);
 
     // Pass 1: validate every step before anything is launched.
     std::vector<gspc::ConvParams> params(n_layers);

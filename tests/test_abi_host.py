@@ -69,6 +69,9 @@ def test_pack_and_conv_reject_bad_arguments_before_any_launch():
     assert lib.gspc_pack_weights(fake, 8, 8, 3, 3, 2, 0, ctypes.c_void_p(256 * 1024 + 4), 1 << 20,
                                  ctypes.byref(h)) == -8
     assert lib.gspc_conv2d_grouped(fake, None, 1, 8, 4, 4, 8, 3, 3, 1, 1, 2, fake) == -1
+    odd = ctypes.c_void_p(256 * 1024 + 4)        # the alignment is checked before the handle is read
+    assert lib.gspc_conv2d_grouped(odd, fake, 1, 8, 4, 4, 8, 3, 3, 1, 1, 2, fake) == -8
+    assert lib.gspc_conv2d_grouped(fake, fake, 1, 8, 4, 4, 8, 3, 3, 1, 1, 2, odd) == -8
     assert lib.gspc_unpack_weights(None, 0, fake) == -1
     assert lib.gspc_packed_info(None, None, None, None, None, None, None, None) == -1
     assert lib.gspc_pack_input_bf16(None, 4, fake) == -1
@@ -84,6 +87,8 @@ def test_chain_rejects_bad_arguments_before_any_launch():
     sizes = (ctypes.c_size_t * 2)(1024, 1024)
     assert lib.gspc_run_layer_chain(None, 1, bufs, sizes, 2, None) == -1
     assert lib.gspc_run_layer_chain(layers, 0, bufs, sizes, 2, None) == -8
+    odd_bufs = (ctypes.c_void_p * 2)(256 * 1024, 512 * 1024 + 8)
+    assert lib.gspc_run_layer_chain(layers, 1, odd_bufs, sizes, 2, None) == -8  # misaligned buffer
     L = layers[0]
     L.op, L.src, L.dst, L.src2 = b.OP_RELU, 0, 5, -1
     L.N, L.Cin, L.H, L.W = 1, 4, 4, 4

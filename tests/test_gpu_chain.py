@@ -111,3 +111,39 @@ def test_graph_mode_off_matches():
     b.gspc_set_graph_mode(1)
     b.gspc_set_stream()
     assert np.array_equal(outs[0], outs[1]) and np.array_equal(outs[1], outs[2])
+
+
+@pytest.mark.parametrize("s", [
+    wl.ConvShape(300, 64, 14, 14, 64, 3, 3, 1, 1, 2),   # more tiles than resident blocks, 16-byte stores
+    wl.ConvShape(40, 64, 7, 7, 64, 3, 3, 1, 1, 2),      # odd width: several images per tile, 4-byte stores
+    wl.ConvShape(3, 64, 56, 56, 64, 3, 3, 1, 1, 2),     # 16-byte loads, row bands with a ragged tail
+    wl.ConvShape(2, 64, 28, 28, 128, 3, 3, 2, 1, 2),    # stride 2
+    wl.ConvShape(5, 256, 12, 12, 256, 3, 3, 1, 1, 2),   # four chunks of channels per group
+], ids=lambda s: "x".join(map(str, s)))
+def test_bf16_conv_with_residual_and_relu(s):
+    """A bf16 convolution step with the residual operand and the ReLU of a
+    basic block (Section IV-A networks), against the oracle on the same
+    rounded operands."""
+    import torch
+    import oracle
+    from paper_2006_09791_amd import binding as b
+    dev = torch.device("cuda:0")
+    b.gspc_set_stream()
+    x = wl.make_input((s.N, s.Cin, s.H, s.W), 41)
+    w = wl.make_weight(s.Cout, s.Cin // s.groups, 3, 3, 42)
+    ho, wo = b.gspc_output_dims(s.H, s.W, 3, 3, s.stride, s.pad)
+    res = wl.make_input((s.N, s.Cout, ho, wo), 43)
+    pw = b.gspc_pack_weights(torch.from_numpy(w).to(dev), s.groups, b.GSPC_BF16)
+    xb = b.gspc_pack_input_bf16(torch.from_numpy(x).to(dev))
+    rd = torch.from_numpy(res).to(dev).reshape(-1)
+    yd = torch.full((res.size,), float("nan"), dtype=torch.float32, device=dev)
+    layer = wl.Layer("conv", 0, 1, 2, s.N, s.Cin, s.H, s.W, s.Cout, 3, 3, s.stride, s.pad, s.groups, True, 0)
+    lc = b.LayerChain([layer], [pw], [xb.reshape(-1), rd, yd])
+    b.gspc_run_layer_chain(lc)
+    torch.cuda.synchronize()
+    assert "mfma16b" in b.gspc_last_kernel()
+    got = yd.cpu().numpy().reshape(res.shape)
+    _, xr = wl.round_to_bf16(x)
+    _, wr = wl.round_to_bf16(w)
+    ref = oracle.relu(oracle.add(oracle.conv2d_grouped(xr, wr, s.stride, s.pad, s.groups, threads=8), res))
+    assert rel_err(got, ref) < 1e-4, b.gspc_last_kernel()
