@@ -137,6 +137,30 @@ int prepare_conv(const void *input, const gspc_packed_t *pw, int N, int Cin, int
     p->KPGd = pw->geom.KPGd;
     p->relu = 0;
     p->in_bf16 = pw->dtype == GSPC_BF16;
+    // A 1x1 convolution with stride 1 and no padding acts on each plane as on flat
+    // memory: when the row length is not a multiple of 4 (14x14, 7x7 planes) but the
+    // plane is, hand the kernels the same bytes as H' x W' with W' % 4 == 0, which
+    // opens their 16-byte staging paths.  W' is the multiple-of-4 divisor of H*W that
+    // fills the staging's power-of-two lane groups best (ties: the longer row).
+    if (KH == 1 && KW == 1 && stride == 1 && pad == 0 && W % 4 != 0 && (H * W) % 4 == 0 && H * W <= 16384) {
+        const int hw = H * W;
+        int best_w = 0;
+        double best_fill = 0.0;
+        for (int w = 4; w <= hw && w <= 256; w += 4) {
+            if (hw % w) continue;
+            int lanes = 1;
+            while (lanes < w / 4) lanes *= 2;
+            const double fill = (double)(w / 4) / lanes;
+            if (fill >= best_fill) {
+                best_fill = fill;
+                best_w = w;
+            }
+        }
+        if (best_w) {
+            p->W = p->Wout = best_w;
+            p->H = p->Hout = hw / best_w;
+        }
+    }
     return GSPC_OK;
 }
 

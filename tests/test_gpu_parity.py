@@ -79,6 +79,9 @@ SWEEP = [
     S(1, 3, 40, 40, 64, 7, 7, 2, 3, 1),    # 7x7 stride 2
     S(2, 32, 32, 32, 64, 1, 1, 2, 0, 1),   # 1x1 stride 2 shortcut
     S(1, 16, 14, 14, 32, 1, 1, 1, 0, 1),   # pointwise
+    S(3, 64, 14, 14, 128, 1, 1, 1, 0, 1),  # pointwise on planes whose rows are not a multiple of 4 wide
+    S(2, 32, 6, 10, 32, 1, 1, 1, 0, 2),    # grouped pointwise, 60-element planes
+    S(5, 32, 7, 7, 64, 1, 1, 1, 0, 1),     # pointwise, odd plane size (no re-pitch possible)
     S(1, 8, 12, 12, 8, 3, 3, 1, 1, 8),     # depthwise
     S(2, 8, 7, 7, 8, 3, 3, 2, 1, 8),       # depthwise stride 2, odd size
     S(1, 8, 9, 9, 16, 3, 3, 1, 1, 8),      # depthwise, channel multiplier 2
