@@ -462,21 +462,30 @@ int gspc_run_layer_chain(const gspc_layer_t *layers, int n_layers, void *const *
         struct Step {
             int first, count;
             gspc::FusedPlan *plan;
+            gspc::DwPwPlan *pair;
         };
         std::vector<Step> steps;
         std::vector<std::unique_ptr<gspc::FusedPlan>> plans;
+        std::vector<std::unique_ptr<gspc::DwPwPlan>> pairs;
         for (int i = 0; i < n_layers;) {
             int covered = 0;
             if (t_fusion && t_force_path == GSPC_PATH_AUTO) {
                 auto pl = std::make_unique<gspc::FusedPlan>();
                 covered = gspc::plan_fused_run(layers, i, n_layers - i, act_bufs, pl.get());
                 if (covered > 0) {
-                    steps.push_back({i, covered, pl.get()});
+                    steps.push_back({i, covered, pl.get(), nullptr});
                     plans.push_back(std::move(pl));
+                } else {
+                    auto pr = std::make_unique<gspc::DwPwPlan>();
+                    covered = gspc::plan_dwpw(layers, i, n_layers - i, act_bufs, pr.get());
+                    if (covered > 0) {
+                        steps.push_back({i, covered, nullptr, pr.get()});
+                        pairs.push_back(std::move(pr));
+                    }
                 }
             }
             if (covered == 0) {
-                steps.push_back({i, 1, nullptr});
+                steps.push_back({i, 1, nullptr, nullptr});
                 covered = 1;
             }
             i += covered;
@@ -487,6 +496,10 @@ int gspc_run_layer_chain(const gspc_layer_t *layers, int n_layers, void *const *
                     const hipError_t e = gspc::launch_fused_run(*st.plan, t_stream, &t_last_kernel);
                     if (e != hipSuccess) return hip_fail(e, "fused run launch");
                     t_last_path = GSPC_PATH_DIRECT;
+                } else if (st.pair) {
+                    const hipError_t e = gspc::launch_dwpw(*st.pair, t_stream, &t_last_kernel);
+                    if (e != hipSuccess) return hip_fail(e, "fused pair launch");
+                    t_last_path = GSPC_PATH_MFMA;
                 } else {
                     const int rc2 = launch_step(st.first);
                     if (rc2 != GSPC_OK) return rc2;

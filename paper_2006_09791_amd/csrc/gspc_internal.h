@@ -143,6 +143,16 @@ struct FusedPlan {
 int plan_fused_run(const gspc_layer_t *layers, int first, int count, void *const *bufs, FusedPlan *out);
 hipError_t launch_fused_run(const FusedPlan &plan, hipStream_t s, const char **name);
 
+// Depthwise 3x3 + pointwise 1x1 pair as one kernel; plan is opaque to the caller.
+struct DwPwPlan {
+    int inst, sd;
+    alignas(8) char params[96];
+    alignas(8) char tile[128];
+};
+// 2 if layers[first], layers[first + 1] run as one fused launch, else 0.
+int plan_dwpw(const gspc_layer_t *layers, int first, int count, void *const *bufs, DwPwPlan *out);
+hipError_t launch_dwpw(const DwPwPlan &plan, hipStream_t s, const char **name);
+
 hipError_t launch_pack_weights(const float *w, const gspc_packed *h, hipStream_t s);
 hipError_t launch_unpack_weights(const gspc_packed *h, int which, float *w, hipStream_t s);
 hipError_t launch_cast_bf16(const float *in, size_t count, uint16_t *out, hipStream_t s);

@@ -68,3 +68,54 @@ def time_layers(shapes, dtype="f32", inner=10, reps=10, rotate=1):
         del bufs, lc
     b.gspc_set_chain_fusion(1)
     return rows
+
+
+def time_blocks(pairs, inner=8, reps=5, rotate=4):
+    """pairs: (depthwise 3x3, pointwise 1x1) workloads.ConvShape pairs, the block of
+    the networks of Section IV-A.  Each block is timed twice inside recorded chains,
+    as two kernels and with chain fusion (one kernel where the pair qualifies).
+    The input and output buffers rotate; the depthwise result has one buffer, which the
+    next block overwrites (as in a network that reuses its activation buffers), so a
+    fused block need not store it.  Bytes are the block's algorithmic ones:
+    input + both weight tensors + pointwise output."""
+    import torch
+    dev = torch.device("cuda:0")
+    b.gspc_set_stream()
+    rows = []
+    for dw, pw in pairs:
+        ho, wo = b.gspc_output_dims(dw.H, dw.W, 3, 3, dw.stride, dw.pad)
+        w1 = torch.randn((dw.Cout, 1, 3, 3), device=dev) * 0.3
+        w2 = torch.randn((pw.Cout, pw.Cin, 1, 1), device=dev) * 0.1
+        packed = [b.gspc_pack_weights(w1, dw.groups), b.gspc_pack_weights(w2, 1)]
+        n_in, n_mid, n_out = dw.N * dw.Cin * dw.H * dw.W, dw.N * dw.Cout * ho * wo, pw.N * pw.Cout * ho * wo
+        bufs = [torch.empty(n_mid, dtype=torch.float32, device=dev)]
+        for _ in range(rotate):
+            bufs += [torch.rand(n_in, device=dev) * 2 - 1, torch.empty(n_out, dtype=torch.float32, device=dev)]
+        layers = []
+        for i in range(inner):
+            r = i % rotate
+            layers.append(wl.Layer("conv", 1 + 2 * r, -1, 0, dw.N, dw.Cin, dw.H, dw.W, dw.Cout, 3, 3,
+                                   dw.stride, dw.pad, dw.groups, True, 0))
+            layers.append(wl.Layer("conv", 0, -1, 2 + 2 * r, pw.N, pw.Cin, ho, wo, pw.Cout, 1, 1, 1, 0, 1, True, 1))
+        lc = b.LayerChain(layers, packed, bufs)
+        row = {"block": f"dw {dw.Cin}@{dw.H}x{dw.W} s{dw.stride} + pw {pw.Cin}->{pw.Cout} N{dw.N}"}
+        macs = wl.conv_macs(dw) + wl.conv_macs(pw)
+        nbytes = (n_in + n_out + dw.Cout * 9 + pw.Cout * pw.Cin) * 4
+        for mode in ("two_kernels", "fused"):
+            b.gspc_set_chain_fusion(1 if mode == "fused" else 0)
+            b.gspc_run_layer_chain(lc)
+            name = b.gspc_last_kernel()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            torch.cuda.synchronize()
+            e0.record()
+            for _ in range(reps):
+                b.gspc_run_layer_chain(lc)
+            e1.record()
+            torch.cuda.synchronize()
+            us = e0.elapsed_time(e1) / (reps * inner) * 1e3
+            row[mode] = {"kernel": name, "us": round(us, 2), "tflops": round(2 * macs / us / 1e6, 2),
+                         "gbs": round(nbytes / us / 1e3, 1)}
+        b.gspc_set_chain_fusion(1)
+        rows.append(row)
+        del bufs, lc
+    return rows

@@ -90,3 +90,48 @@ def test_replays_are_stable():
             assert np.array_equal(eager[ch.out_buf][:n_out], again), f"replay {rep}"
             (torch.randn(1 << 16, device="cuda") * 2).sum().item()
     b.gspc_set_stream()
+
+
+# ---- depthwise 3x3 + pointwise 1x1 as one kernel ------------------------------------
+
+def _dwpw_chain(N, C, C2, hw, stride, relu_dw=True, relu_pw=True, residual=False, reuse=False):
+    """dw 3x3 (buffer 0 -> 1), pw 1x1 (1 -> 2); optionally a residual operand for the
+    pointwise step (buffer 3, filled by an extra step) and a last step that overwrites the
+    depthwise buffer, so that its contents after the pair cannot be observed."""
+    ch = wl.Chain(f"dwpw{N}_{C}_{C2}_{hw}_{stride}", (N, C, hw, hw))
+    ho = wl.out_size(hw, 3, stride, 1)
+    res = -1
+    if residual:
+        ch.conv(0, 3, N, C, hw, hw, C2, 1, stride, 0, 1)          # any tensor of the output's shape
+        res = 3
+    ch.conv(0, 1, N, C, hw, hw, C, 3, stride, 1, C, relu=relu_dw)
+    ch.conv(1, 2, N, C, ho, ho, C2, 1, 1, 0, 1, relu=relu_pw, residual=res)
+    if reuse:
+        ch.conv(2, 1, N, C2, ho, ho, C, 1, 1, 0, 1)
+    return ch
+
+
+@pytest.mark.parametrize("N,C,C2,hw,stride,kw", [
+    (2, 32, 64, 112, 1, {}),                          # first MobileNet block, row bands of 2 rows
+    (3, 64, 128, 56, 2, {}),                          # stride 2, two filter tiles recompute the tile
+    (5, 32, 64, 12, 1, dict(relu_dw=False)),          # several images per block, ragged last block
+    (2, 128, 128, 28, 1, dict(relu_pw=False, residual=True)),
+    (2, 64, 64, 16, 2, dict(reuse=True)),             # depthwise buffer overwritten later: not stored
+    (1, 16, 32, 8, 1, dict(reuse=True, residual=True)),
+], ids=lambda v: str(v) if not isinstance(v, dict) else "-".join(v) or "plain")
+def test_depthwise_pointwise_fused(N, C, C2, hw, stride, kw):
+    ch = _dwpw_chain(N, C, C2, hw, stride, **kw)
+    weights = ch.make_weights(6)
+    x0 = wl.make_input(ch.input_shape, wl.make_seed(6, C, hw))
+    ref = oracle_chain(ch, x0, weights)
+    fused, name = _run(ch, x0, weights, 1)
+    plain, name2 = _run(ch, x0, weights, 0)
+    assert "conv_dwpw" not in name2
+    if not kw.get("reuse"):
+        assert "conv_dwpw" in name, name
+    # every buffer ends up as the step-by-step execution (and the oracle) leaves it
+    for k, (a, c) in enumerate(zip(fused, plain)):
+        n = ch.buf_elems[k]
+        assert rel_err(a[:n], c[:n]) < TOL_F32, f"buffer {k}"
+        assert rel_err(a[:n], np.asarray(ref[k]).reshape(-1)[:n]) < TOL_F32, f"buffer {k} vs oracle"
+
