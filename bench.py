@@ -52,7 +52,7 @@ def main():
     ap.add_argument("--traffic-probe", action="store_true",
                     help="first run a plain 256 MiB device copy three times: the known-size kernel "
                          "against which rocprofv3's FETCH_SIZE / WRITE_SIZE counters are scaled")
-    ap.add_argument("--sweep", choices=["wrn", "wrn_n256", "resnet_bf16", "depthwise", "latency"],
+    ap.add_argument("--sweep", choices=["wrn", "wrn_n256", "resnet_bf16", "depthwise", "blocks", "latency"],
                     help="instead of the headline step, time every layer of a configuration family "
                          "and print one JSON line with a row per layer")
     ap.add_argument("--fusion", action="store_true",
@@ -118,6 +118,9 @@ def main():
                 ms = (time.perf_counter() - ta) / reps * 1e3
                 rows.append({"network": name, "layers": len(ch.layers), "mmacs": round(ch.macs() / 1e6, 2),
                              "latency_ms": round(ms, 4), "gmacs": round(ch.macs() / ms / 1e6, 1)})
+        elif args.sweep == "blocks":
+            # depthwise 3x3 + pointwise 1x1 blocks, as two kernels and with chain fusion
+            rows = layer_timing.time_blocks(wl.depthwise_pairs(256), inner=8, reps=5)
         elif args.sweep == "resnet_bf16":
             shapes = [s for g in (2, 8, 32) for s in wl.resnet34_grouped_shapes(256, g)]
             rows = layer_timing.time_layers(shapes, "bf16", inner=4, reps=5)

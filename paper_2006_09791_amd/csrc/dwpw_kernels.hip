@@ -417,7 +417,9 @@ static_assert(sizeof(TileP) <= sizeof(((DwPwPlan *)0)->tile), "plan storage too 
 // pair runs as one kernel.  The depthwise result is written to its buffer only if the
 // rest of the chain can still see it.
 int plan_dwpw(const gspc_layer_t *layers, int first, int count, void *const *bufs, DwPwPlan *out) {
-    static const bool off = std::getenv("GSPC_NO_DWPW") != nullptr;   // tuning aid
+    static const bool off = std::getenv("GSPC_NO_DWPW") != nullptr;   // tuning aids
+    static const int force_ocb = std::getenv("GSPC_DWPW_OCB") ? std::atoi(std::getenv("GSPC_DWPW_OCB")) : 0;
+    static const int max_c = std::getenv("GSPC_DWPW_C") ? std::atoi(std::getenv("GSPC_DWPW_C")) : 128;
     if (off || count < 2) return 0;
     const gspc_layer_t &A = layers[first], &B = layers[first + 1];
     if (A.op != GSPC_OP_CONV || B.op != GSPC_OP_CONV || !A.w || !B.w) return 0;
@@ -430,7 +432,7 @@ int plan_dwpw(const gspc_layer_t *layers, int first, int count, void *const *buf
         B.Cin != A.Cout || B.H != H || B.W != W)
         return 0;
     if (B.dst == A.dst || B.dst == A.src || B.src2 == A.dst) return 0;
-    if (A.Cin % 4 || A.Cin > 128 || B.Cout % 16 || W % 4 || A.W % 4) return 0;
+    if (A.Cin % 4 || A.Cin > max_c || B.Cout % 16 || W % 4 || A.W % 4) return 0;
     if (A.stride == 2 && A.W != 2 * W) return 0;
     if (B.w->geom.variant != kMfma16 || !B.w->geom.mfma_bytes) return 0;
     auto misaligned = [](const void *q) { return (reinterpret_cast<uintptr_t>(q) & 15) != 0; };
@@ -459,24 +461,28 @@ int plan_dwpw(const gspc_layer_t *layers, int first, int count, void *const *buf
     }
     p.d = keep ? static_cast<float *>(bufs[A.dst]) : nullptr;
 
-    // every filter tile of the pointwise layer recomputes the depthwise tile: fuse only
-    // while that is at most two of them
+    // Every filter tile of the pointwise layer recomputes the depthwise tile: fuse only while
+    // that is at most two of them (four at stride 2, where a depthwise output costs the same
+    // but the unfused pair moves four times the input per output).  Measured break-even.
+    const int max_ocb = force_ocb ? force_ocb : (A.stride == 2 ? 4 : 2);
+    // The largest tile that still gives every compute unit two blocks, else the shape with the
+    // most blocks; with less than one block per compute unit the pair is faster as two
+    // kernels, whose finer tiles spread over more of the chip (small batches).
     int best = -1;
+    long best_blocks = 0;
     TileP bt{};
     for (int i = 0; i < kNumCfgP; ++i) {
         TileP t;
-        if (!planP_cfg(p, A.stride, kCfgP[i], &t) || t.oc_blocks > 2) continue;
+        if (!planP_cfg(p, A.stride, kCfgP[i], &t) || t.oc_blocks > max_ocb) continue;
         const long blocks = (long)t.tiles * t.oc_blocks;
-        if (best < 0 || blocks >= 2 * kNumCU) {
-            const bool enough = blocks >= 2 * kNumCU;
-            if (best < 0 || enough) {
-                best = i;
-                bt = t;
-            }
-            if (enough) break;
+        if (blocks > best_blocks) {
+            best = i;
+            best_blocks = blocks;
+            bt = t;
         }
+        if (blocks >= 2 * kNumCU) break;
     }
-    if (best < 0) return 0;
+    if (best < 0 || best_blocks < kNumCU) return 0;
     out->inst = best;
     out->sd = A.stride;
     std::memcpy(out->params, &p, sizeof(p));
