@@ -98,6 +98,8 @@ def main():
             rows = []
             nets = [(f"wrn40x2-style g={g}", wl.wrn_chain(1, g), 2) for g in GROUPS]
             nets += [(f"resnet34-shaped g={g}", wl.resnet34_chain(1, g), 3) for g in (2, 4, 8, 16, 32)]
+            nets += [(f"mobilenet-shaped {'G(N) depthwise' if g is None else 'g=' + str(g)}", wl.mobilenet_chain(1, g), 5)
+                     for g in (2, 4, 8, 16, None)]
             nets += [(f"depthwise+pointwise C={C} {hw}x{hw} s{st}", wl.mobilenet_dw_chain(1, C, hw, st), 4)
                      for C, hw in wl.DEPTHWISE_CH_HW for st in (1, 2)]
             for name, ch, cfg in nets:

@@ -107,8 +107,11 @@ bool plan_dw_planes(const ConvParams &p, DwPlan *out) {
     pb = pb > 64 ? 64 : pb;
     pb -= pb % 4;
     if (pb < 4) return false;
-    t.PB = pb;
     const double planes = (double)p.N * p.Cin;
+    // small batches: fewer planes per block rather than idle compute units
+    const long spread = (long)(planes / (2 * kNumCU));
+    if (spread < pb) pb = spread < 4 ? 4 : (int)(spread - spread % 4);
+    t.PB = pb;
     const double xb = planes * t.HW * 4, yb = planes * t.HoWo * 4, wb = (double)p.groups * 9 * p.KPGd * 4;
     if (planes >= 2147483648.0 || xb >= (double)kOob || yb >= (double)kOob || wb >= (double)kOob) return false;
     // fast_div exactness: numerator * divisor < 2^32 at each step

@@ -201,6 +201,30 @@ def resnet34_chain(N, g):
     return ch
 
 
+# (channels in, channels out, stride) of the 13 blocks of a MobileNet-shaped ImageNet body
+MOBILENET_BLOCKS = [(32, 64, 1), (64, 128, 2), (128, 128, 1), (128, 256, 2), (256, 256, 1), (256, 512, 2),
+                    (512, 512, 1), (512, 512, 1), (512, 512, 1), (512, 512, 1), (512, 512, 1),
+                    (512, 1024, 2), (1024, 1024, 1)]
+
+
+def mobilenet_chain(N, g=None, hw=224):
+    """MobileNet-shaped stack in the form of the paper's networks (Section IV-A): a 3x3
+    stride-2 stem 3 -> 32, then 13 blocks of a grouped 3x3 convolution a -> a followed by
+    a pointwise 1x1 convolution a -> b.  g = None is the depthwise extreme G(N) (g = a);
+    otherwise every 3x3 convolution of the body has g groups.  Two activation buffers
+    alternate, so the 3x3 result of a block is overwritten two steps later."""
+    tag = "dw" if g is None else f"g{g}"
+    ch = Chain(f"mobilenet_{tag}_n{N}", (N, 3, hw, hw))
+    h, _ = ch.conv(0, 1, N, 3, hw, hw, 32, 3, 2, 1, 1, relu=True)
+    cur = 1
+    for a, b_, s in MOBILENET_BLOCKS:
+        mid, out = (2, 3) if cur == 1 else ((1, 3) if cur == 2 else (1, 2))
+        ho, _ = ch.conv(cur, mid, N, a, h, h, a, 3, s, 1, a if g is None else g, relu=True)
+        ch.conv(mid, out, N, a, ho, ho, b_, 1, 1, 0, 1, relu=True)
+        cur, h = out, ho
+    return ch
+
+
 def mobilenet_dw_chain(N, C, hw, stride):
     """Depthwise 3x3 (g = C) followed by a pointwise 1x1 C -> 2C."""
     ch = Chain(f"dw_c{C}_hw{hw}_s{stride}_n{N}", (N, C, hw, hw))

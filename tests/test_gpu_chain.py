@@ -147,3 +147,14 @@ def test_bf16_conv_with_residual_and_relu(s):
     _, wr = wl.round_to_bf16(w)
     ref = oracle.relu(oracle.add(oracle.conv2d_grouped(xr, wr, s.stride, s.pad, s.groups, threads=8), res))
     assert rel_err(got, ref) < 1e-4, b.gspc_last_kernel()
+
+
+@pytest.mark.parametrize("N,g", [(1, None), (1, 8), (8, None)], ids=["n1-depthwise", "n1-g8", "n8-depthwise"])
+def test_mobilenet_chain(N, g):
+    """MobileNet-shaped stack in the paper's block form (grouped 3x3 a -> a, pointwise
+    a -> b), depthwise extreme and a G(8) variant; at N = 8 the first blocks run as fused
+    depthwise + pointwise kernels."""
+    chain = wl.mobilenet_chain(N, g)
+    got, ref = _run(chain, 5, wl.make_seed(5, N, 0 if g is None else g))
+    assert np.abs(ref).max() > 0
+    assert rel_err(got, ref) < TOL_F32

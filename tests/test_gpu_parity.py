@@ -82,6 +82,9 @@ SWEEP = [
     S(3, 64, 14, 14, 128, 1, 1, 1, 0, 1),  # pointwise on planes whose rows are not a multiple of 4 wide
     S(2, 32, 6, 10, 32, 1, 1, 1, 0, 2),    # grouped pointwise, 60-element planes
     S(5, 32, 7, 7, 64, 1, 1, 1, 0, 1),     # pointwise, odd plane size (no re-pitch possible)
+    S(300, 32, 16, 16, 32, 3, 3, 1, 1, 8),  # 4 filters per group, several waves of blocks
+    S(520, 16, 9, 12, 32, 3, 3, 2, 1, 4),   # 8 filters per group, stride 2, odd height, large batch
+    S(700, 16, 7, 7, 16, 3, 3, 1, 1, 4),    # 7x7 planes: scalar staging, several images per tile, ragged tail
     S(1, 8, 12, 12, 8, 3, 3, 1, 1, 8),     # depthwise
     S(2, 8, 7, 7, 8, 3, 3, 2, 1, 8),       # depthwise stride 2, odd size
     S(1, 8, 9, 9, 16, 3, 3, 1, 1, 8),      # depthwise, channel multiplier 2
