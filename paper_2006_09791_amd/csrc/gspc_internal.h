@@ -84,6 +84,11 @@ hipError_t launch_mfma(const ConvParams &p, const PackGeom &g, hipStream_t s,
                        const char **name);
 bool mfma_supported(const ConvParams &p, const PackGeom &g);
 
+// Offline tile table (GSPC_TUNE_FILE, see tune_table.cpp): family letter forced for this layer
+// ('\0' = none) and the configuration index forced within a family (-1 = none).
+char tuned_family(const ConvParams &p);
+int tuned_config(const ConvParams &p, char family);
+
 // bf16 16x16x32 MFMA kernel; plan is opaque to the caller.
 struct MfmaB16Plan {
     int inst;

@@ -330,14 +330,22 @@ bool plan_mfma4(const ConvParams &p, const PackGeom &g, Mfma4Plan *out) {
     // images share nothing, so packing several into a block only costs blocks.
     int chosen = 0;
     Tile4 best{};
+    int forced = force ? std::atoi(force) : tuned_config(p, 'q');
+    {
+        Tile4 t;
+        if (!force && forced >= 0 && ((forced != 1 && forced != 2 && forced != 4) || !plan4_tile(p, g, forced, &t))) forced = -1;
+    }
     for (int nt : {4, 2, 1}) {
         Tile4 t;
-        if (force && std::atoi(force) != nt) continue;
+        if (forced >= 0 && forced != nt) continue;
         if (!plan4_tile(p, g, nt, &t)) continue;
         const long blocks = (long)t.row_blocks * t.img_blocks * p.groups;
         chosen = nt;
         best = t;
-        if (t.NB == 1 && blocks >= kNumCU / 2) break;
+        // heavy filter banks (8 channels x 8 filters per group: 144 MFMAs per pixel run) want
+        // the launch spread over more, shorter blocks (autotuner: 10.6 -> 8.9 us at N = 64)
+        const long enough = g.Kred * MT >= 144 ? 4L * kNumCU : kNumCU / 2;
+        if (t.NB == 1 && blocks >= enough) break;
     }
     if (!chosen) return false;
     out->inst = chosen;

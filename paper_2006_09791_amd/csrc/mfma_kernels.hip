@@ -425,8 +425,9 @@ bool plan16_cfg(const ConvParams &p, const PackGeom &g, const Cfg16 &c, Tile16 *
 bool plan16(const ConvParams &p, const PackGeom &g, int *cfg_idx, Tile16 *t_out) {
     if (g.variant != kMfma16 || !p.wm || !shape_instantiated(p.KH, p.KW, p.stride)) return false;
     static const char *force = std::getenv("GSPC_TILE16");
-    if (force) {
-        const int i = std::atoi(force);
+    const int forced = force ? std::atoi(force) : tuned_config(p, 'm');
+    if (forced >= 0) {
+        const int i = forced;
         if (i >= 0 && i < kNumCfg16 && plan16_cfg(p, g, kCfg16[i], t_out)) {
             *cfg_idx = i;
             return true;
@@ -559,7 +560,9 @@ const Plan &get_plan(const ConvParams &p, const PackGeom &g) {
     auto it = cache.find(k);
     if (it != cache.end()) return it->second;
     Plan pl{};
+    const char fam = tuned_family(p);   // offline tile table: may prefer the plain 16x16x4 kernel
     if (plan_mfma_bf16(p, g, &pl.pb)) pl.kind = 32;
+    else if (fam == 'm' && plan16(p, g, &pl.idx, &pl.t16)) pl.kind = 16;
     else if (plan_mfma16w(p, g, &pl.pw)) pl.kind = 17;
     else if (plan16(p, g, &pl.idx, &pl.t16)) pl.kind = 16;
     else if (plan_mfma4(p, g, &pl.p4)) pl.kind = 4;

@@ -542,12 +542,17 @@ bool plan_mfma_bf16(const ConvParams &p, const PackGeom &g, MfmaB16Plan *out) {
     if (!p.in_bf16 || !p.wb || !g.bf16_bytes || p.KH != 3 || p.KW != 3 || (p.stride != 1 && p.stride != 2))
         return false;
     static const char *force = std::getenv("GSPC_TILEB");
+    int forced = force ? std::atoi(force) : tuned_config(p, 'b');
+    {
+        TileB t;
+        if (!force && forced >= 0 && (forced >= kNumCfgB || !planB_cfg(p, g, kCfgB[forced], &t))) forced = -1;
+    }
     int best = -1;
     long best_blocks = -1;
     TileB bt{};
     for (int i = 0; i < kNumCfgB; ++i) {
         TileB t;
-        if (force && std::atoi(force) != i) continue;
+        if (forced >= 0 && forced != i) continue;
         if (!planB_cfg(p, g, kCfgB[i], &t)) continue;
         const long blocks = (long)t.row_blocks * t.img_blocks * t.oc_blocks * p.groups;
         if (blocks >= 4 * kNumCU) {

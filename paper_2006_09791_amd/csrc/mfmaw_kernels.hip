@@ -550,14 +550,23 @@ bool plan_mfma16w(const ConvParams &p, const PackGeom &g, Mfma16wPlan *out) {
     if (off || g.variant != kMfma16 || !p.wm || p.in_bf16 || p.KH != 3 || p.KW != 3 ||
         (p.stride != 1 && p.stride != 2) || p.W % 4 || g.CPG % 4 || g.CPGp != g.CPG)
         return false;
+    // Stride-2 layers with at most 8 channels per group: the plain 16x16x4 kernel is faster
+    // (6-20 % on the stage-entry layers of the WRN stack, found by the tile-table autotuner),
+    // unless a table asks for this kernel.
+    if (p.stride == 2 && g.CPG <= 8 && tuned_family(p) != 'w') return false;
     static const char *force = std::getenv("GSPC_TILEW");
     const int ckb = g.CPG % 8 == 0 ? 2 : 1;
+    int forced = force ? std::atoi(force) : tuned_config(p, 'w');
+    {
+        Tile16w t;
+        if (!force && forced >= 0 && (forced >= kNumCfgW || !planW_cfg(p, g, kCfgW[forced], ckb, &t))) forced = -1;
+    }
     int best = -1;
     long best_waves = -1;
     Tile16w bt{};
     for (int i = 0; i < kNumCfgW; ++i) {
         Tile16w t;
-        if (force && std::atoi(force) != i) continue;
+        if (forced >= 0 && forced != i) continue;
         if (!planW_cfg(p, g, kCfgW[i], ckb, &t)) continue;
         const long waves = (long)t.wave_tiles * t.oc_blocks * p.groups;
         if (waves >= 4 * kNumCU) {   // every SIMD has a wave: take the largest such tile

@@ -110,3 +110,17 @@ def test_product_path_does_not_import_the_oracle():
                 text = open(os.path.join(dirpath, f)).read()
                 assert not re.search(r"^\s*(import|from)\s+oracle|liboracle|oracle_conv|#include.*oracle",
                                      text, flags=re.M), f"{f} reaches into the oracle"
+
+
+def test_autotuner_table_lines_parse_back():
+    """The autotuner's table format (one layer per line: ten shape integers, dtype, family
+    letter, index) is what the library's reader expects: 13 whitespace-separated fields."""
+    from paper_2006_09791_amd import autotune, workloads as wl
+    s = wl.ConvShape(64, 32, 32, 32, 64, 3, 3, 2, 1, 4)
+    line = autotune.table_line(s, "f32", "m", 7)
+    f = line.split()
+    assert len(f) == 13 and [int(v) for v in f[:11]] == [64, 32, 32, 32, 64, 3, 3, 2, 1, 4, 0]
+    assert f[11] == "m" and f[12] == "7"
+    assert autotune.table_line(s, "bf16", "b", 0).split()[10] == "1"
+    shapes, dtype = autotune.workload_shapes("resnet34_bf16", 256)
+    assert dtype == "bf16" and len(shapes) == 21

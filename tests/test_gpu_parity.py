@@ -217,3 +217,34 @@ def test_mismatch_and_errors_on_device(gpu):
     with pytest.raises(b.GspcError) as e:
         b.gspc_conv2d_grouped(x, pw, 1, 8, 1, 1, 8, 3, 3, 1, 0, 2, y)
     assert e.value.code == -2
+
+
+def test_tile_table_overrides_the_planner(gpu, tmp_path):
+    """A process started with GSPC_TUNE_FILE takes the table's kernel family and tile for
+    the listed layer (and still matches the oracle); unlisted layers are untouched."""
+    import subprocess, sys, os, textwrap
+    s = S(4, 64, 16, 16, 64, 3, 3, 1, 1, 2)
+    table = tmp_path / "t.tune"
+    table.write_text("# test table\n4 64 16 16 64 3 3 1 1 2 0 m 8\n")
+    code = textwrap.dedent(f"""
+        import sys, numpy as np
+        sys.path.insert(0, {os.path.dirname(os.path.dirname(os.path.abspath(__file__)))!r})
+        sys.path.insert(0, {os.path.dirname(os.path.abspath(__file__))!r})
+        import torch, oracle
+        from paper_2006_09791_amd import binding as b, workloads as wl
+        from helpers import rel_err
+        S = wl.ConvShape
+        for s in (S(4, 64, 16, 16, 64, 3, 3, 1, 1, 2), S(4, 64, 16, 16, 64, 3, 3, 1, 1, 4)):
+            x = wl.make_input((s.N, s.Cin, s.H, s.W), 3); w = wl.make_weight(s.Cout, s.Cin // s.groups, 3, 3, 4)
+            pw = b.gspc_pack_weights(torch.from_numpy(w).cuda(), s.groups)
+            y = torch.empty((s.N, s.Cout, s.H, s.W), device="cuda")
+            b.gspc_conv2d_grouped(torch.from_numpy(x).cuda(), pw, s.N, s.Cin, s.H, s.W, s.Cout, 3, 3, 1, 1, s.groups, y)
+            torch.cuda.synchronize()
+            err = rel_err(y.cpu().numpy(), oracle.conv2d_grouped(x, w, 1, 1, s.groups))
+            print(b.gspc_last_kernel(), err < 1e-4)
+    """)
+    env = dict(os.environ, GSPC_TUNE_FILE=str(table))
+    out = subprocess.run([sys.executable, "-c", code], env=env, check=True, capture_output=True, text=True).stdout
+    lines = [l for l in out.strip().splitlines() if l.startswith("conv_")]
+    assert lines[0].startswith("conv_mfma16<1,1,1,4,3,3,1,f32>") and lines[0].endswith("True"), out
+    assert lines[1].startswith("conv_mfma16w<") and lines[1].endswith("True"), out
