@@ -345,7 +345,8 @@ bool plan_mfma4(const ConvParams &p, const PackGeom &g, Mfma4Plan *out) {
         // heavy filter banks (8 channels x 8 filters per group: 144 MFMAs per pixel run) want
         // the launch spread over more, shorter blocks (autotuner: 10.6 -> 8.9 us at N = 64)
         const long enough = g.Kred * MT >= 144 ? 4L * kNumCU : kNumCU / 2;
-        if (t.NB == 1 && blocks >= enough) break;
+        // several images per block only when the launch is plentiful anyway (large batches)
+        if ((t.NB == 1 && blocks >= enough) || blocks >= 4L * kNumCU) break;
     }
     if (!chosen) return false;
     out->inst = chosen;

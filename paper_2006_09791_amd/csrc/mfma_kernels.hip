@@ -445,7 +445,7 @@ bool plan16(const ConvParams &p, const PackGeom &g, int *cfg_idx, Tile16 *t_out)
             *t_out = t;
             return true;
         }
-        if (blocks > best_blocks) {
+        if (blocks >= best_blocks) {   // equal block counts: the smaller tile (less padding)
             best_blocks = blocks;
             best = i;
             bt = t;
@@ -455,15 +455,25 @@ bool plan16(const ConvParams &p, const PackGeom &g, int *cfg_idx, Tile16 *t_out)
     // the waves of a block split the reduction instead of the pixels.
     static const bool no_ksplit = std::getenv("GSPC_NO_KSPLIT") != nullptr;
     if (!no_ksplit && best_blocks < 2 * kNumCU && g.ksteps >= 36) {
+        int kbest = -1;
+        long kblocks = -1;
+        Tile16 kt{};
         for (int i = kFirstKsplit; i < kNumCfg16; ++i) {
             Tile16 t;
             if (!plan16_cfg(p, g, kCfg16[i], &t)) continue;
             const long blocks = (long)t.row_blocks * t.img_blocks * t.oc_blocks * p.groups;
-            if (blocks >= kNumCU || i == kNumCfg16 - 1) {
-                *cfg_idx = i;
-                *t_out = t;
-                return true;
+            if (blocks > kblocks) {
+                kbest = i;
+                kblocks = blocks;
+                kt = t;
             }
+            if (blocks >= kNumCU) break;   // the largest tile that gives every compute unit a block
+        }
+        // else the split shape with the most blocks, if that is more than without splitting
+        if (kbest >= 0 && (kblocks >= kNumCU || kblocks > best_blocks)) {
+            *cfg_idx = kbest;
+            *t_out = kt;
+            return true;
         }
     }
     if (best < 0) {

@@ -550,10 +550,11 @@ bool plan_mfma16w(const ConvParams &p, const PackGeom &g, Mfma16wPlan *out) {
     if (off || g.variant != kMfma16 || !p.wm || p.in_bf16 || p.KH != 3 || p.KW != 3 ||
         (p.stride != 1 && p.stride != 2) || p.W % 4 || g.CPG % 4 || g.CPGp != g.CPG)
         return false;
-    // Stride-2 layers with at most 8 channels per group: the plain 16x16x4 kernel is faster
-    // (6-20 % on the stage-entry layers of the WRN stack, found by the tile-table autotuner),
-    // unless a table asks for this kernel.
-    if (p.stride == 2 && g.CPG <= 8 && tuned_family(p) != 'w') return false;
+    // Findings of the tile-table autotuner, unless a table asks for this kernel: stride-2 layers
+    // run faster on the plain 16x16x4 kernel (this one has only its smallest tile for them:
+    // 6-20 % at N = 64 with few channels per group, 10-20 % at N = 256 for every g).
+    const bool asked = tuned_family(p) == 'w';
+    if (p.stride == 2 && !asked && (g.CPG <= 8 || p.N >= 128)) return false;
     static const char *force = std::getenv("GSPC_TILEW");
     const int ckb = g.CPG % 8 == 0 ? 2 : 1;
     int forced = force ? std::atoi(force) : tuned_config(p, 'w');
@@ -571,6 +572,7 @@ bool plan_mfma16w(const ConvParams &p, const PackGeom &g, Mfma16wPlan *out) {
         const long waves = (long)t.wave_tiles * t.oc_blocks * p.groups;
         if (waves >= 4 * kNumCU) {   // every SIMD has a wave: take the largest such tile
             best = i;
+            best_waves = waves;
             bt = t;
             break;
         }
@@ -581,6 +583,9 @@ bool plan_mfma16w(const ConvParams &p, const PackGeom &g, Mfma16wPlan *out) {
         }
     }
     if (best < 0) return false;
+    // Fewer than two waves per compute unit and a long reduction (batch 1): the plain kernel, which
+    // then lets the four waves of a block split the reduction, is 10-15 % faster.
+    if (!asked && !force && best_waves >= 0 && best_waves < 2 * kNumCU && g.ksteps >= 36) return false;
     out->inst = best;
     out->ckb = ckb;
     static_assert(sizeof(Tile16w) <= sizeof(out->data), "plan storage too small");

@@ -223,9 +223,8 @@ def test_tile_table_overrides_the_planner(gpu, tmp_path):
     """A process started with GSPC_TUNE_FILE takes the table's kernel family and tile for
     the listed layer (and still matches the oracle); unlisted layers are untouched."""
     import subprocess, sys, os, textwrap
-    s = S(4, 64, 16, 16, 64, 3, 3, 1, 1, 2)
     table = tmp_path / "t.tune"
-    table.write_text("# test table\n4 64 16 16 64 3 3 1 1 2 0 m 8\n")
+    table.write_text("# test table\n64 64 16 16 64 3 3 1 1 2 0 m 8\n")
     code = textwrap.dedent(f"""
         import sys, numpy as np
         sys.path.insert(0, {os.path.dirname(os.path.dirname(os.path.abspath(__file__)))!r})
@@ -234,13 +233,13 @@ def test_tile_table_overrides_the_planner(gpu, tmp_path):
         from paper_2006_09791_amd import binding as b, workloads as wl
         from helpers import rel_err
         S = wl.ConvShape
-        for s in (S(4, 64, 16, 16, 64, 3, 3, 1, 1, 2), S(4, 64, 16, 16, 64, 3, 3, 1, 1, 4)):
+        for s in (S(64, 64, 16, 16, 64, 3, 3, 1, 1, 2), S(64, 64, 16, 16, 64, 3, 3, 1, 1, 4)):
             x = wl.make_input((s.N, s.Cin, s.H, s.W), 3); w = wl.make_weight(s.Cout, s.Cin // s.groups, 3, 3, 4)
             pw = b.gspc_pack_weights(torch.from_numpy(w).cuda(), s.groups)
             y = torch.empty((s.N, s.Cout, s.H, s.W), device="cuda")
             b.gspc_conv2d_grouped(torch.from_numpy(x).cuda(), pw, s.N, s.Cin, s.H, s.W, s.Cout, 3, 3, 1, 1, s.groups, y)
             torch.cuda.synchronize()
-            err = rel_err(y.cpu().numpy(), oracle.conv2d_grouped(x, w, 1, 1, s.groups))
+            err = rel_err(y.cpu().numpy(), oracle.conv2d_grouped(x, w, 1, 1, s.groups, threads=8))
             print(b.gspc_last_kernel(), err < 1e-4)
     """)
     env = dict(os.environ, GSPC_TUNE_FILE=str(table))
