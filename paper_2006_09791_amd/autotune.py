@@ -37,6 +37,8 @@ def workload_shapes(name, batch):
         return [s for g in (1, 2, 4, 8, 16) for s in wl.wrn_grouped_shapes(batch, g)], "f32"
     if name == "resnet34":
         return [s for g in (2, 4, 8, 16, 32) for s in wl.resnet34_grouped_shapes(batch, g)], "f32"
+    if name == "mobilenet_pw":
+        return [pw for _, pw in wl.depthwise_pairs(batch)], "f32"
     if name == "resnet34_bf16":
         return [s for g in (2, 8, 32) for s in wl.resnet34_grouped_shapes(batch, g)], "bf16"
     raise SystemExit(f"unknown workload {name}")
@@ -71,7 +73,7 @@ def run_child(args, table_path):
 
 def main():
     ap = argparse.ArgumentParser(description=__doc__, formatter_class=argparse.RawDescriptionHelpFormatter)
-    ap.add_argument("--workload", default="wrn", choices=["wrn", "resnet34", "resnet34_bf16"])
+    ap.add_argument("--workload", default="wrn", choices=["wrn", "resnet34", "resnet34_bf16", "mobilenet_pw"])
     ap.add_argument("--batch", type=int, default=64)
     ap.add_argument("--inner", type=int, default=10)
     ap.add_argument("--reps", type=int, default=5)

@@ -436,20 +436,45 @@ bool plan16(const ConvParams &p, const PackGeom &g, int *cfg_idx, Tile16 *t_out)
     int best = -1;
     long best_blocks = -1;
     Tile16 bt{};
+    // Among the shapes that fill the chip (four blocks per compute unit), the one whose pixel
+    // tiles waste the fewest lanes (a 28x28 plane is 4 tiles of 256 pixels, the last one nearly
+    // empty, but exactly 7 tiles of 128: 20 % faster); ties go to the larger shape.
+    int full = -1, roomy = -1;
+    double full_eff = 0.0;
+    Tile16 ft{}, rt{};
     for (int i = 0; i < kFirstKsplit; ++i) {
         Tile16 t;
         if (!plan16_cfg(p, g, kCfg16[i], &t)) continue;
         const long blocks = (long)t.row_blocks * t.img_blocks * t.oc_blocks * p.groups;
         if (blocks >= 4 * kNumCU) {
-            *cfg_idx = i;
-            *t_out = t;
-            return true;
+            const Cfg16 &c = kCfg16[i];
+            const double eff = (double)p.N * p.Hout * p.Wout /
+                               ((double)t.row_blocks * t.img_blocks * 16 * c.NI * c.WP);
+            // (only while a wave keeps at least 8 MFMA tiles: smaller shapes lose more in operand reuse)
+            if (full < 0 || (eff > full_eff + 0.02 && c.MI * c.NI >= 8)) {
+                full = i;
+                full_eff = eff;
+                ft = t;
+            }
+            continue;
+        }
+        if (full >= 0) continue;
+        // Smaller launches: the largest shape that still gives 1.5 blocks per compute unit
+        // (the autotuner's picks at batch 1 all sit there), else the one with the most blocks.
+        if (roomy < 0 && blocks >= 3 * kNumCU / 2) {
+            roomy = i;
+            rt = t;
         }
         if (blocks >= best_blocks) {   // equal block counts: the smaller tile (less padding)
             best_blocks = blocks;
             best = i;
             bt = t;
         }
+    }
+    if (full >= 0) {
+        *cfg_idx = full;
+        *t_out = ft;
+        return true;
     }
     // Too few blocks to fill the GPU and a long reduction (small batches): let
     // the waves of a block split the reduction instead of the pixels.
@@ -462,15 +487,15 @@ bool plan16(const ConvParams &p, const PackGeom &g, int *cfg_idx, Tile16 *t_out)
             Tile16 t;
             if (!plan16_cfg(p, g, kCfg16[i], &t)) continue;
             const long blocks = (long)t.row_blocks * t.img_blocks * t.oc_blocks * p.groups;
-            if (blocks > kblocks) {
+            if (blocks >= kblocks) {   // equal counts: the smaller tile
                 kbest = i;
                 kblocks = blocks;
                 kt = t;
             }
-            if (blocks >= kNumCU) break;   // the largest tile that gives every compute unit a block
+            if (blocks >= 3 * kNumCU / 2) break;   // the largest tile that gives 1.5 blocks per compute unit
         }
-        // else the split shape with the most blocks, if that is more than without splitting
-        if (kbest >= 0 && (kblocks >= kNumCU || kblocks > best_blocks)) {
+        // else the split shape with the most blocks, unless not splitting gives more
+        if (kbest >= 0 && (kblocks >= kNumCU || kblocks >= best_blocks)) {
             *cfg_idx = kbest;
             *t_out = kt;
             return true;
@@ -486,6 +511,11 @@ bool plan16(const ConvParams &p, const PackGeom &g, int *cfg_idx, Tile16 *t_out)
             }
         }
         return false;
+    }
+    if (roomy >= 0) {
+        *cfg_idx = roomy;
+        *t_out = rt;
+        return true;
     }
     *cfg_idx = best;
     *t_out = bt;

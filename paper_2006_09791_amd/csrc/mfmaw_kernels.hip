@@ -550,11 +550,12 @@ bool plan_mfma16w(const ConvParams &p, const PackGeom &g, Mfma16wPlan *out) {
     if (off || g.variant != kMfma16 || !p.wm || p.in_bf16 || p.KH != 3 || p.KW != 3 ||
         (p.stride != 1 && p.stride != 2) || p.W % 4 || g.CPG % 4 || g.CPGp != g.CPG)
         return false;
-    // Findings of the tile-table autotuner, unless a table asks for this kernel: stride-2 layers
-    // run faster on the plain 16x16x4 kernel (this one has only its smallest tile for them:
-    // 6-20 % at N = 64 with few channels per group, 10-20 % at N = 256 for every g).
+    // Findings of the tile-table autotuner for stride-2 layers, for which this kernel has only
+    // its smallest tile: the plain 16x16x4 kernel is 6-20 % faster with at most 8 channels per
+    // group, 10-20 % faster at batch 256 and 10-25 % faster at batch 16 and below; in between
+    // (batch 64, more channels per group) this one wins by up to 30 %.  A table can overrule.
     const bool asked = tuned_family(p) == 'w';
-    if (p.stride == 2 && !asked && (g.CPG <= 8 || p.N >= 128)) return false;
+    if (p.stride == 2 && !asked && (g.CPG <= 8 || p.N >= 128 || p.N <= 16)) return false;
     static const char *force = std::getenv("GSPC_TILEW");
     const int ckb = g.CPG % 8 == 0 ? 2 : 1;
     int forced = force ? std::atoi(force) : tuned_config(p, 'w');
