@@ -87,7 +87,9 @@ static hipError_t launch_generic(const ConvParams &p, hipStream_t s) {
 // registers.  Requires pad = 1, Wout a multiple of 4 and, for stride 2, W = 2*Wout.
 // ---------------------------------------------------------------------------
 struct TileS {
-    int SPR, RG;            // strips per output row, row groups per plane
+    int SPR, RG;            // strip slots per output row (see SPRv), row groups per plane
+    int SPRv;               // strips that exist; SPR is rounded up to a divisor of 64 so that a row's
+                            // strips never straddle a wavefront (the surplus lanes idle)
     int total;              // threads with work
     int shfl;               // strips of a row never straddle a wave: neighbours by shuffle
     unsigned m_spr, m_rg, m_g;
@@ -100,9 +102,9 @@ __global__ __launch_bounds__(256) void conv_direct_small(ConvParams p, TileS t) 
     constexpr int IR = S == 1 ? R + 2 : 2 * R + 1;   // input rows per strip
     constexpr int NV = S;                            // 16-byte loads per input row
     const unsigned gt = blockIdx.x * 256 + threadIdx.x;
-    const bool live = gt < (unsigned)t.total;
-    const unsigned g0 = live ? gt : 0;
+    const unsigned g0 = gt < (unsigned)t.total ? gt : 0;
     const unsigned srow = fast_div(g0, t.m_spr), colv = g0 - srow * t.SPR;
+    const bool live = gt < (unsigned)t.total && colv < (unsigned)t.SPRv;
     const unsigned plane = fast_div(srow, t.m_rg), rg = srow - plane * t.RG;
     const unsigned n = fast_div(plane, t.m_g), j = plane - n * p.groups;
     const int oh0 = rg * R, ih0 = oh0 * S - 1;
@@ -126,7 +128,7 @@ __global__ __launch_bounds__(256) void conv_direct_small(ConvParams p, TileS t) 
 #pragma unroll
             for (int x = 0; x < 4; ++x) acc[o][r][x] = 0.f;
 
-    const bool has_left = colv > 0, has_right = colv + 1 < (unsigned)t.SPR;
+    const bool has_left = colv > 0, has_right = colv + 1 < (unsigned)t.SPRv;
 #pragma unroll
     for (int c = 0; c < CPG; ++c) {
         const unsigned cbase = ((n * p.Cin + j * CPG + c) * p.H) * p.W;
@@ -300,7 +302,12 @@ bool plan_small(const ConvParams &p, TileS *out) {
     if (!inst) return false;
     const int R = p.stride == 1 ? 4 : 2;
     TileS t{};
-    t.SPR = p.Wout / 4;
+    t.SPRv = p.Wout / 4;
+    t.SPR = t.SPRv;
+    if (t.SPR <= 64 && 64 % t.SPR) {   // e.g. 14 strips of a 56-wide row take 16 lanes
+        t.SPR = 1;
+        while (t.SPR < t.SPRv) t.SPR *= 2;
+    }
     t.RG = (p.Hout + R - 1) / R;
     const double total = (double)p.N * p.groups * t.RG * t.SPR;
     const double xb = (double)p.N * p.Cin * p.H * p.W * (p.in_bf16 ? 2 : 4);
