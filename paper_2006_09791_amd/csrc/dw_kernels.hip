@@ -17,7 +17,7 @@
 namespace gspc {
 
 struct TileD {
-    int PB;                 // planes per block (multiple of 4)
+    int PB;                 // planes per block (4, 8, ..., 64)
     int LWp, PL;            // tile row pitch (W+2) and floats per plane tile ((H+2)*(W+2), rounded up to 4)
     int HW, HoWo;
     unsigned planes;        // N * C
@@ -71,24 +71,29 @@ __global__ __launch_bounds__(256) void conv_direct_dw(ConvParams p, TileD t) {
         }
     }
     __syncthreads();
-    // ---- outputs: element plane0*HoWo + o, consecutive lanes -> consecutive o ----
+    // ---- outputs: 256 / PB threads per plane (PB is a power of two), so that a thread keeps its
+    // plane's nine weights in registers; the lanes of a plane produce consecutive elements ----
     const __amdgpu_buffer_rsrc_t ry = make_rsrc(p.y, t.y_bytes);
     const __amdgpu_buffer_rsrc_t rr = make_rsrc(p.res ? p.res : p.y, t.y_bytes);
-    const int ototal = np * t.HoWo;
-    const unsigned obase = plane0 * t.HoWo * 4;
-    for (int o = tid; o < ototal; o += 256) {
-        const int pl = fast_div(o, t.m_HoWo), r = o - pl * t.HoWo;
-        const int oh = fast_div(r, t.m_Wout), ow = r - oh * p.Wout;
-        const float *ip = tile + pl * t.PL + oh * S * t.LWp + ow * S;
-        const float *wp = wl + pl * 9;
-        float acc = 0.f;
+    const int tpp = 256 / t.PB, pl = tid / tpp, sub = tid - pl * tpp;
+    if (pl < np) {
+        float w[9];
 #pragma unroll
-        for (int kh = 0; kh < 3; ++kh)
+        for (int k = 0; k < 9; ++k) w[k] = wl[pl * 9 + k];
+        const float *tp = tile + pl * t.PL;
+        const unsigned obase = (plane0 + pl) * t.HoWo * 4;
+        for (int o = sub; o < t.HoWo; o += tpp) {
+            const int oh = fast_div(o, t.m_Wout), ow = o - oh * p.Wout;
+            const float *ip = tp + oh * S * t.LWp + ow * S;
+            float acc = 0.f;
 #pragma unroll
-            for (int kw = 0; kw < 3; ++kw) acc = fmaf(ip[kh * t.LWp + kw], wp[kh * 3 + kw], acc);
-        if (p.res) acc += __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rr, obase + o * 4, 0, 0));
-        if (p.relu) acc = fmaxf(acc, 0.f);
-        __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(acc), ry, obase + o * 4, 0, 0);
+            for (int kh = 0; kh < 3; ++kh)
+#pragma unroll
+                for (int kw = 0; kw < 3; ++kw) acc = fmaf(ip[kh * t.LWp + kw], w[kh * 3 + kw], acc);
+            if (p.res) acc += __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rr, obase + o * 4, 0, 0));
+            if (p.relu) acc = fmaxf(acc, 0.f);
+            __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(acc), ry, obase + o * 4, 0, 0);
+        }
     }
 }
 
@@ -104,13 +109,21 @@ bool plan_dw_planes(const ConvParams &p, DwPlan *out) {
     t.HoWo = p.Hout * p.Wout;
     // as many planes as fit 32 KB of tiles, at most 64, a multiple of 4
     int pb = (32 * 1024 / 4) / t.PL;
-    pb = pb > 64 ? 64 : pb;
-    pb -= pb % 4;
+    // measured: 8 planes per block for planes of 14x14 and more (32 threads per plane: 128-byte
+    // store segments), 32 for smaller ones
+    static const int pb_force = std::getenv("GSPC_DW_PB") ? std::atoi(std::getenv("GSPC_DW_PB")) : 0;   // tuning aid
+    const int pb_cap = pb_force ? pb_force : (t.HW >= 128 ? 8 : 32);
+    pb = pb > pb_cap ? pb_cap : pb;
     if (pb < 4) return false;
+    {
+        int q = 4;   // a power of two: the block's 256 threads divide evenly over the planes
+        while (2 * q <= pb) q *= 2;
+        pb = q;
+    }
     const double planes = (double)p.N * p.Cin;
     // small batches: fewer planes per block rather than idle compute units
     const long spread = (long)(planes / (2 * kNumCU));
-    if (spread < pb) pb = spread < 4 ? 4 : (int)(spread - spread % 4);
+    while (pb > 4 && spread < pb) pb /= 2;
     t.PB = pb;
     const double xb = planes * t.HW * 4, yb = planes * t.HoWo * 4, wb = (double)p.groups * 9 * p.KPGd * 4;
     if (planes >= 2147483648.0 || xb >= (double)kOob || yb >= (double)kOob || wb >= (double)kOob) return false;
