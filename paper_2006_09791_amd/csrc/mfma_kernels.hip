@@ -42,6 +42,7 @@ struct Tile16 {
     int ksteps, mtiles;      // geometry of the packed weight section
     int in_floats, w_floats; // per LDS buffer (a buffer is in | w | 4 spare floats)
     int ksplit;              // 1: the four waves share one pixel tile and split the reduction
+    int vec_out;             // groups of four tile pixels are 16 contiguous, aligned bytes of a plane
     unsigned m_IHt, m_NB, m_ppi, m_Wout, m_rowb, m_ocb;  // multiply-high reciprocals (0 = divisor 1)
     unsigned x_bytes, w_bytes, y_bytes;                  // extents for the buffer descriptors
 };
@@ -57,7 +58,7 @@ __device__ unsigned long long g_phase[8 * 4096];
 #define GSPC_STAMP(i)
 #endif
 
-template <int MI, int NI, int WM, int WP, int KH, int KW, int S, typename TIN>
+template <int MI, int NI, int WM, int WP, int KH, int KW, int S, typename TIN, bool VO>
 __global__ __launch_bounds__(64 * WM * WP) void conv_mfma16(ConvParams p, Tile16 t) {
     GSPC_STAMP(0)
     constexpr int NT = 64 * WM * WP, TAPS = KH * KW, MIWM = MI * WM;
@@ -162,10 +163,22 @@ __global__ __launch_bounds__(64 * WM * WP) void conv_mfma16(ConvParams p, Tile16
         const int img = fast_div(qq, t.m_ppi), rem = qq - img * ppi;
         const int r = fast_div(rem, t.m_Wout), col = rem - r * p.Wout;
         base[ni] = (lane >> 4) * t.PLANE + img * t.IMG + r * S * t.LW + (t.XO - p.pad) + col * S;
-        const int n = n0 + img, oh = oh0 + r;
-        ooff[ni] = (q < tot && n < p.N && oh < p.Hout)
-                       ? (((unsigned)n * p.Cout + j * p.KPG + 4 * (lane >> 4)) * HWo + oh * p.Wout + col) * 4
-                       : kOob;
+        if (VO) {
+            // pixels are the rows of the MFMA product: this lane ends up with pixels 4*(l/16) .. +3
+            // of the run, four consecutive elements of one output plane, for filter l % 16
+            const int q0 = (wp * NI + ni) * 16 + 4 * (lane >> 4);
+            const int qq0 = q0 < tot ? q0 : 0;
+            const int img0 = fast_div(qq0, t.m_ppi), rem0 = qq0 - img0 * ppi;
+            const unsigned n = n0 + img0, e = oh0 * p.Wout + rem0;
+            ooff[ni] = (q0 < tot && n < (unsigned)p.N && e < HWo)
+                           ? ((n * p.Cout + j * p.KPG + (lane & 15)) * HWo + e) * 4
+                           : kOob;
+        } else {
+            const int n = n0 + img, oh = oh0 + r;
+            ooff[ni] = (q < tot && n < p.N && oh < p.Hout)
+                           ? (((unsigned)n * p.Cout + j * p.KPG + 4 * (lane >> 4)) * HWo + oh * p.Wout + col) * 4
+                           : kOob;
+        }
     }
 
     f32x4 acc[MI][NI];
@@ -215,7 +228,8 @@ __global__ __launch_bounds__(64 * WM * WP) void conv_mfma16(ConvParams p, Tile16
                     for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
                         for (int ni = 0; ni < NI; ++ni)
-                            acc[mi][ni] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[mi], b[ni], acc[mi][ni], 0, 0, 0);
+                            acc[mi][ni] = VO ? __builtin_amdgcn_mfma_f32_16x16x4f32(b[ni], a[mi], acc[mi][ni], 0, 0, 0)
+                                             : __builtin_amdgcn_mfma_f32_16x16x4f32(a[mi], b[ni], acc[mi][ni], 0, 0, 0);
                 }
             }
         }
@@ -265,6 +279,42 @@ __global__ __launch_bounds__(64 * WM * WP) void conv_mfma16(ConvParams p, Tile16
     // this lane's pixel; the 4*(lane/16) part already sits in ooff.
     const __amdgpu_buffer_rsrc_t ry = make_rsrc(p.y, t.y_bytes);
     const unsigned oc0 = (ob * MIWM + wm * MI) * 16;
+    if (VO) {
+        // one 16-byte store per tile: a quarter of the store instructions, and the vector memory
+        // path charges per instruction
+        if (p.res) {
+            const __amdgpu_buffer_rsrc_t rr = make_rsrc(p.res, t.y_bytes);
+            f32x4 rv[MI][NI];
+#pragma unroll
+            for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+                for (int ni = 0; ni < NI; ++ni)
+                    rv[mi][ni] = __builtin_bit_cast(
+                        f32x4, __builtin_amdgcn_raw_buffer_load_b128(rr, ooff[ni], (oc0 + mi * 16) * HWo * 4, 0));
+#pragma unroll
+            for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+                for (int ni = 0; ni < NI; ++ni) acc[mi][ni] += rv[mi][ni];
+        }
+        if (p.relu) {
+#pragma unroll
+            for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+                for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) acc[mi][ni][r] = fmaxf(acc[mi][ni][r], 0.f);
+        }
+        // the stores read the accumulators in place; nothing writes a register after them
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+            for (int ni = 0; ni < NI; ++ni)
+                __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, acc[mi][ni]), ry, ooff[ni],
+                                                       (oc0 + mi * 16) * HWo * 4, 0);
+        GSPC_STAMP(6)
+        return;
+    }
     if (p.res) {
         const __amdgpu_buffer_rsrc_t rr = make_rsrc(p.res, t.y_bytes);
 #pragma unroll
@@ -400,6 +450,7 @@ bool plan16_cfg(const ConvParams &p, const PackGeom &g, const Cfg16 &c, Tile16 *
     t.m_Wout = div_magic(p.Wout);
     t.m_rowb = div_magic(t.row_blocks);
     t.m_ocb = div_magic(t.oc_blocks);
+    t.vec_out = (t.TH * p.Wout) % 4 == 0 && (p.Hout * p.Wout) % 4 == 0;
     t.tasks = t.CK * t.NB * t.IHt;
     t.xslots = (t.tasks + rpp - 1) / rpp;
     t.wslots = (c.MI * c.WM * best * taps * 16 + NT - 1) / NT;
@@ -522,12 +573,12 @@ bool plan16(const ConvParams &p, const PackGeom &g, int *cfg_idx, Tile16 *t_out)
     return true;
 }
 
-template <int MI, int NI, int WM, int WP, int KH, int KW, int S, typename TIN>
-hipError_t launch16_inst(const ConvParams &p, const Tile16 &t, hipStream_t s) {
+template <int MI, int NI, int WM, int WP, int KH, int KW, int S, typename TIN, bool VO>
+hipError_t launch16_vo(const ConvParams &p, const Tile16 &t, hipStream_t s) {
     size_t lds = 2 * ((size_t)t.in_floats + t.w_floats + 4) * sizeof(float);
     if (t.ksplit && lds < (size_t)WM * WP * MI * NI * 1024) lds = (size_t)WM * WP * MI * NI * 1024;
     dim3 grid(t.row_blocks * t.img_blocks, p.groups * t.oc_blocks);
-    auto kern = conv_mfma16<MI, NI, WM, WP, KH, KW, S, TIN>;
+    auto kern = conv_mfma16<MI, NI, WM, WP, KH, KW, S, TIN, VO>;
     if (lds > 64 * 1024) {
         static thread_local size_t allowed = 0;   // per instantiation and thread
         if (lds > allowed) {
@@ -539,6 +590,15 @@ hipError_t launch16_inst(const ConvParams &p, const Tile16 &t, hipStream_t s) {
     }
     hipLaunchKernelGGL(kern, grid, dim3(64 * WM * WP), lds, s, p, t);
     return hipGetLastError();
+}
+
+template <int MI, int NI, int WM, int WP, int KH, int KW, int S, typename TIN>
+hipError_t launch16_inst(const ConvParams &p, const Tile16 &t, hipStream_t s) {
+    if constexpr (KH == 7)   // the stem: one layer per network, not worth a second instantiation
+        return launch16_vo<MI, NI, WM, WP, KH, KW, S, TIN, false>(p, t, s);
+    else
+        return t.vec_out ? launch16_vo<MI, NI, WM, WP, KH, KW, S, TIN, true>(p, t, s)
+                         : launch16_vo<MI, NI, WM, WP, KH, KW, S, TIN, false>(p, t, s);
 }
 
 template <int MI, int NI, int WM, int WP, typename TIN>
@@ -620,7 +680,8 @@ hipError_t launch_mfma(const ConvParams &p, const PackGeom &g, hipStream_t s, co
         *name = intern_name("conv_mfma16<" + std::to_string(c.MI) + "," + std::to_string(c.NI) + "," +
                             std::to_string(c.WM) + "," + std::to_string(c.WP) + "," + std::to_string(p.KH) +
                             "," + std::to_string(p.KW) + "," + std::to_string(p.stride) +
-                            (p.in_bf16 ? ",bf16>" : ",f32>") + (c.ksplit ? "/ksplit" : ""));
+                            (p.in_bf16 ? ",bf16," : ",f32,") + (pl.t16.vec_out && p.KH != 7 ? "true>" : "false>") +
+                            (c.ksplit ? "/ksplit" : ""));
         return p.in_bf16 ? launch16_cfg<uint16_t>(pl.idx, p, pl.t16, s) : launch16_cfg<float>(pl.idx, p, pl.t16, s);
     }
     if (pl.kind == 32) return launch_mfma_bf16(p, g, pl.pb, s, name);

@@ -245,5 +245,5 @@ def test_tile_table_overrides_the_planner(gpu, tmp_path):
     env = dict(os.environ, GSPC_TUNE_FILE=str(table))
     out = subprocess.run([sys.executable, "-c", code], env=env, check=True, capture_output=True, text=True).stdout
     lines = [l for l in out.strip().splitlines() if l.startswith("conv_")]
-    assert lines[0].startswith("conv_mfma16<1,1,1,4,3,3,1,f32>") and lines[0].endswith("True"), out
+    assert lines[0].startswith("conv_mfma16<1,1,1,4,3,3,1,f32,") and lines[0].endswith("True"), out
     assert lines[1].startswith("conv_mfma16w<") and lines[1].endswith("True"), out
