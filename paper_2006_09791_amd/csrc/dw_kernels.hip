@@ -9,6 +9,10 @@
 // consecutive across the wavefront, so the stores are contiguous as well.
 // Nothing depends on W being a multiple of 4 or on the plane filling a
 // wavefront (14x14 and 7x7 planes, odd strides of planes).  HBM-bound.
+//
+// For the plane widths of the MobileNet / ResNet tails (WT = 28, 14, 7) a thread produces a whole
+// output row: three tile rows pass through registers once, no index arithmetic per output, and
+// the row leaves as 16-, 8- or 4-byte stores; other widths take one output per thread and step.
 #include <cstdlib>
 #include <cstring>
 
@@ -21,11 +25,13 @@ struct TileD {
     int LWp, PL;            // tile row pitch (W+2) and floats per plane tile ((H+2)*(W+2), rounded up to 4)
     int HW, HoWo;
     unsigned planes;        // N * C
-    unsigned m_HW, m_W, m_HoWo, m_Wout, m_C;
+    unsigned m_HW, m_W, m_HoWo, m_Wout, m_C, m_Hout;
     unsigned x_bytes, y_bytes, w_bytes;
 };
 
-template <int S>
+constexpr int kDwSlots = 8;   // 16-byte loads per thread: 32 KB of tiles at most
+
+template <int S, int WT>
 __global__ __launch_bounds__(256) void conv_direct_dw(ConvParams p, TileD t) {
     extern __shared__ f32x4 smem4[];
     float *tile = reinterpret_cast<float *>(smem4);
@@ -37,6 +43,17 @@ __global__ __launch_bounds__(256) void conv_direct_dw(ConvParams p, TileD t) {
     const __amdgpu_buffer_rsrc_t rx = make_rsrc(p.x, t.x_bytes);
     const __amdgpu_buffer_rsrc_t rw = make_rsrc(p.wd, t.w_bytes);
 
+    // ---- the block's planes: one contiguous piece of np*HW floats, requested first so that the
+    // memory latency passes while the tiles are cleared.  Elements past the tensor's end read
+    // as zero (the range check covers the vector offset) and are not used. ----
+    const int total = np * t.HW;
+    const unsigned gbase = plane0 * t.HW * 4;   // 16-byte aligned: PB is a multiple of 4
+    f32x4 pin[kDwSlots];
+#pragma unroll
+    for (int k = 0; k < kDwSlots; ++k) {
+        const int e4 = (tid + k * 256) * 4;
+        pin[k] = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(rx, e4 < total ? gbase + e4 * 4 : kOob, 0, 0));
+    }
     // ---- clear the tiles (the halo must be zero; the interior is overwritten) ----
     {
         const int n4 = t.PB * t.PL / 4;
@@ -51,30 +68,87 @@ __global__ __launch_bounds__(256) void conv_direct_dw(ConvParams p, TileD t) {
         wl[i] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rw, ((c * 9 + k) * p.KPGd) * 4, 0, 0));
     }
     __syncthreads();
-    // ---- the block's planes: one contiguous piece of np*HW floats ---------------
-    {
-        const int total = np * t.HW;
-        const unsigned gbase = plane0 * t.HW * 4;   // 16-byte aligned: PB is a multiple of 4
-        for (int e4 = tid * 4; e4 < total; e4 += 1024) {
-            // elements past the tensor's end read as zero (the range check covers the vector offset)
-            // and are not written
-            const f32x4 v = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(rx, gbase + e4 * 4, 0, 0));
 #pragma unroll
-            for (int k = 0; k < 4; ++k) {
-                const int e = e4 + k;
-                if (e < total) {
-                    const int pl = fast_div(e, t.m_HW), r = e - pl * t.HW;
-                    const int h = fast_div(r, t.m_W), w = r - h * p.W;
-                    tile[pl * t.PL + (h + 1) * t.LWp + (w + 1)] = v[k];
-                }
+    for (int k = 0; k < kDwSlots; ++k) {
+        const int e4 = (tid + k * 256) * 4;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int e = e4 + i;
+            if (e < total) {
+                const int pl = fast_div(e, t.m_HW), r = e - pl * t.HW;
+                const int h = fast_div(r, t.m_W), w = r - h * p.W;
+                tile[pl * t.PL + (h + 1) * t.LWp + (w + 1)] = pin[k][i];
             }
         }
     }
     __syncthreads();
-    // ---- outputs: 256 / PB threads per plane (PB is a power of two), so that a thread keeps its
-    // plane's nine weights in registers; the lanes of a plane produce consecutive elements ----
     const __amdgpu_buffer_rsrc_t ry = make_rsrc(p.y, t.y_bytes);
     const __amdgpu_buffer_rsrc_t rr = make_rsrc(p.res ? p.res : p.y, t.y_bytes);
+    if constexpr (WT > 0) {
+        // ---- a thread per output row of a plane ----
+        constexpr int WO = (WT - 1) / S + 1, LW = WT + 2;
+        const int rows = np * p.Hout;
+        for (int row = tid; row < rows; row += 256) {
+            const int pl = fast_div(row, t.m_Hout), oh = row - pl * p.Hout;
+            float w[9];
+#pragma unroll
+            for (int k = 0; k < 9; ++k) w[k] = wl[pl * 9 + k];
+            float acc[WO];
+#pragma unroll
+            for (int x = 0; x < WO; ++x) acc[x] = 0.f;
+            const float *ip = tile + pl * t.PL + oh * S * LW;
+#pragma unroll
+            for (int kh = 0; kh < 3; ++kh) {
+                float xr[LW];
+                if (LW % 2 == 0) {   // tile rows start on 8-byte boundaries when the pitch is even
+#pragma unroll
+                    for (int x = 0; x < LW; x += 2) {
+                        const float2 v = *reinterpret_cast<const float2 *>(ip + kh * LW + x);
+                        xr[x] = v.x;
+                        xr[x + 1] = v.y;
+                    }
+                } else {
+#pragma unroll
+                    for (int x = 0; x < LW; ++x) xr[x] = ip[kh * LW + x];
+                }
+#pragma unroll
+                for (int kw = 0; kw < 3; ++kw)
+#pragma unroll
+                    for (int x = 0; x < WO; ++x) acc[x] = fmaf(xr[x * S + kw], w[kh * 3 + kw], acc[x]);
+            }
+            const unsigned ob = ((plane0 + pl) * t.HoWo + oh * WO) * 4;
+            constexpr int VW = WO % 4 == 0 ? 4 : WO % 2 == 0 ? 2 : 1;   // the row start is VW*4-byte aligned
+#pragma unroll
+            for (int x = 0; x < WO; x += VW) {
+                if (VW == 4) {
+                    f32x4 v = f32x4{acc[x], acc[x + 1], acc[x + 2], acc[x + 3]};
+                    if (p.res) v += __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(rr, ob + x * 4, 0, 0));
+                    if (p.relu) v = f32x4{fmaxf(v.x, 0.f), fmaxf(v.y, 0.f), fmaxf(v.z, 0.f), fmaxf(v.w, 0.f)};
+                    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, v), ry, ob + x * 4, 0, 0);
+                } else if (VW == 2) {
+                    float a0 = acc[x], a1 = acc[x + 1];
+                    if (p.res) {
+                        const u32x2 rv = __builtin_amdgcn_raw_buffer_load_b64(rr, ob + x * 4, 0, 0);
+                        a0 += __uint_as_float(rv.x);
+                        a1 += __uint_as_float(rv.y);
+                    }
+                    if (p.relu) {
+                        a0 = fmaxf(a0, 0.f);
+                        a1 = fmaxf(a1, 0.f);
+                    }
+                    __builtin_amdgcn_raw_buffer_store_b64(u32x2{__float_as_uint(a0), __float_as_uint(a1)}, ry, ob + x * 4, 0, 0);
+                } else {
+                    float a0 = acc[x];
+                    if (p.res) a0 += __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rr, ob + x * 4, 0, 0));
+                    if (p.relu) a0 = fmaxf(a0, 0.f);
+                    __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(a0), ry, ob + x * 4, 0, 0);
+                }
+            }
+        }
+        return;
+    }
+    // ---- any width: 256 / PB threads per plane (PB is a power of two), so that a thread keeps its
+    // plane's nine weights in registers; the lanes of a plane produce consecutive elements ----
     const int tpp = 256 / t.PB, pl = tid / tpp, sub = tid - pl * tpp;
     if (pl < np) {
         float w[9];
@@ -109,10 +183,10 @@ bool plan_dw_planes(const ConvParams &p, DwPlan *out) {
     t.HoWo = p.Hout * p.Wout;
     // as many planes as fit 32 KB of tiles, at most 64, a multiple of 4
     int pb = (32 * 1024 / 4) / t.PL;
-    // measured: 8 planes per block for planes of 14x14 and more (32 threads per plane: 128-byte
-    // store segments), 32 for smaller ones
+    // measured: 8 planes per block for planes of 28x28 and more (32 threads per plane: 128-byte
+    // store segments), 16 for 14x14, 32 for smaller ones
     static const int pb_force = std::getenv("GSPC_DW_PB") ? std::atoi(std::getenv("GSPC_DW_PB")) : 0;   // tuning aid
-    const int pb_cap = pb_force ? pb_force : (t.HW >= 128 ? 8 : 32);
+    const int pb_cap = pb_force ? pb_force : (t.HW >= 512 ? 8 : t.HW >= 128 ? 16 : 32);
     pb = pb > pb_cap ? pb_cap : pb;
     if (pb < 4) return false;
     {
@@ -137,6 +211,7 @@ bool plan_dw_planes(const ConvParams &p, DwPlan *out) {
     t.m_HoWo = div_magic(t.HoWo);
     t.m_Wout = div_magic(p.Wout);
     t.m_C = div_magic(p.Cin);
+    t.m_Hout = div_magic(p.Hout);
     t.x_bytes = (unsigned)xb;
     t.y_bytes = (unsigned)yb;
     t.w_bytes = (unsigned)wb;
@@ -145,19 +220,34 @@ bool plan_dw_planes(const ConvParams &p, DwPlan *out) {
     return true;
 }
 
+namespace {
+
+template <int S, int WT>
+hipError_t launch_dw_inst(const ConvParams &p, const TileD &t, hipStream_t s) {
+    const size_t lds = ((size_t)t.PB * t.PL + (size_t)t.PB * 9 + 4) * sizeof(float);
+    const dim3 grid((t.planes + t.PB - 1) / t.PB);
+    hipLaunchKernelGGL((conv_direct_dw<S, WT>), grid, dim3(256), lds, s, p, t);
+    return hipGetLastError();
+}
+
+// Measured at N = 256: a thread per output row pays for stride 2 at widths 28 and 7 (the row's
+// few outputs leave in one or two stores); for stride 1 and for width 14 the per-plane split is
+// as fast or faster.
+inline int dw_row_width(const ConvParams &p) {
+    static const bool generic = std::getenv("GSPC_DW_GENERIC") != nullptr;   // tuning aid
+    return (!generic && p.stride == 2 && (p.W == 28 || p.W == 7)) ? p.W : 0;
+}
+
+}  // namespace
+
 hipError_t launch_dw_planes(const ConvParams &p, const DwPlan &plan, hipStream_t s, const char **name) {
     TileD t;
     std::memcpy(&t, plan.data, sizeof(t));
-    const size_t lds = ((size_t)t.PB * t.PL + (size_t)t.PB * 9 + 4) * sizeof(float);
-    const dim3 grid((t.planes + t.PB - 1) / t.PB);
-    if (p.stride == 1) {
-        *name = "conv_direct_dw<1,f32>";
-        hipLaunchKernelGGL(conv_direct_dw<1>, grid, dim3(256), lds, s, p, t);
-    } else {
-        *name = "conv_direct_dw<2,f32>";
-        hipLaunchKernelGGL(conv_direct_dw<2>, grid, dim3(256), lds, s, p, t);
-    }
-    return hipGetLastError();
+    const int wt = dw_row_width(p);
+    *name = intern_name("conv_direct_dw<" + std::to_string(p.stride) + "," + std::to_string(wt) + ",f32>");
+    if (wt == 28) return launch_dw_inst<2, 28>(p, t, s);
+    if (wt == 7) return launch_dw_inst<2, 7>(p, t, s);
+    return p.stride == 1 ? launch_dw_inst<1, 0>(p, t, s) : launch_dw_inst<2, 0>(p, t, s);
 }
 
 }  // namespace gspc
