@@ -100,6 +100,10 @@ def main():
             nets += [(f"resnet34-shaped g={g}", wl.resnet34_chain(1, g), 3) for g in (2, 4, 8, 16, 32)]
             nets += [(f"mobilenet-shaped {'G(N) depthwise' if g is None else 'g=' + str(g)}", wl.mobilenet_chain(1, g), 5)
                      for g in (2, 4, 8, 16, None)]
+            nets += [(f"mobilenetv2-shaped {'G(N) depthwise' if g is None else 'g=' + str(g)}", wl.mobilenetv2_chain(1, g), 6)
+                     for g in (2, 4, 8, 16, None)]
+            nets += [(f"wrn40x2 pointwise form g={g}", wl.wrn_chain(1, g, pointwise=True), 7) for g in (2, 4, 8, 16)]
+            nets += [(f"resnet34 pointwise form g={g}", wl.resnet34_chain(1, g, pointwise=True), 7) for g in (2, 4, 8, 16, 32)]
             nets += [(f"depthwise+pointwise C={C} {hw}x{hw} s{st}", wl.mobilenet_dw_chain(1, C, hw, st), 4)
                      for C, hw in wl.DEPTHWISE_CH_HW for st in (1, 2)]
             for name, ch, cfg in nets:

@@ -194,11 +194,14 @@ PackGeom make_pack_geom(int Cin, int Cout, int KH, int KW, int groups, int dtype
     if (g.KPG % 16 == 0) g.variant = kMfma16;
     else if (g.KPG % 4 == 0) g.variant = kMfma4;
     else g.variant = kMfmaNone;
-    if (g.variant == kMfma16) {
+    // The 16x16x4 operand section: filter tiles of 16, the last one zero-padded.  Below five
+    // filters per group a tile would be more than two thirds padding: those layers stay on
+    // the direct kernels.
+    if (g.variant == kMfma16 || g.KPG >= 5) {
         g.ksub = 4;
         g.CPGp = round_up(g.CPG, g.ksub);
         g.ksteps = g.CPGp / g.ksub * KH * KW;
-        g.mtiles = g.KPG / 16;
+        g.mtiles = (g.KPG + 15) / 16;
         g.mfma_bytes = (size_t)groups * g.mtiles * g.ksteps * 64 * sizeof(float);
     }
     g.mfma_offset = (g.direct_bytes + 255) / 256 * 256;

@@ -25,13 +25,15 @@ inline int round_up(int v, int m) { return (v + m - 1) / m * m; }
 // Geometry of the two sections of a packed-weight buffer.
 //   direct section : fp32 [g][Kred][KPGd], Kred = CPG*KH*KW ordered (c, kh, kw),
 //                    KPGd = KPG rounded up to a multiple of 4, zero padded.
-//   mfma section   : (variant 16 only) fp32 [g][ksteps][KPG/16][64], the A operand
+//   mfma section   : (KPG >= 5) fp32 [g][ksteps][ceil(KPG/16)][64], the A operand
 //                    of one v_mfma_f32_16x16x4_f32 per (k-step, filter tile,
 //                    lane); k-steps ordered (c / 4, kh, kw) with CPG zero-padded
 //                    to a multiple of 4; lane l holds filter l % 16 of its tile
-//                    at reduction slot c = cblk*4 + l / 16.
-//   Variant 4 (KPG a multiple of 4 but not of 16) runs the 4x4x1 MFMA kernel,
-//   which reads its operands from the direct section.
+//                    at reduction slot c = cblk*4 + l / 16; filters past KPG in
+//                    the last tile are zero.
+//   variant 16 = KPG a multiple of 16 (no padding filters).  Variant 4 (KPG a
+//   multiple of 4 but not of 16) can also run the 4x4x1 MFMA kernel, which
+//   reads its operands from the direct section.
 struct PackGeom {
     int CPG, KPG, Kred, KPGd;
     int variant;   // MfmaVariant

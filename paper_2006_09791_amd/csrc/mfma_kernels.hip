@@ -16,7 +16,7 @@
 namespace gspc {
 
 // ---------------------------------------------------------------------------
-// 16x16x4 kernel: KPG a multiple of 16.
+// 16x16x4 kernel: filters in tiles of 16 (the last tile zero-padded when KPG is not a multiple).
 //
 // v_mfma_f32_16x16x4_f32 operand layout (lane l of 64):
 //   A: filter row l%16, reduction slot l/16      B: slot l/16, pixel column l%16
@@ -279,7 +279,12 @@ __global__ __launch_bounds__(64 * WM * WP) void conv_mfma16(ConvParams p, Tile16
     // this lane's pixel; the 4*(lane/16) part already sits in ooff.
     const __amdgpu_buffer_rsrc_t ry = make_rsrc(p.y, t.y_bytes);
     const unsigned oc0 = (ob * MIWM + wm * MI) * 16;
+    // KPG need not be a multiple of 16: the last filter tile is zero-padded in the packed
+    // section, and the lanes (registers) of its padding filters get an out-of-range offset.
     if (VO) {
+        unsigned om[MI];
+#pragma unroll
+        for (int mi = 0; mi < MI; ++mi) om[mi] = oc0 + mi * 16 + (lane & 15) < (unsigned)p.KPG ? 0u : kOob;
         // one 16-byte store per tile: a quarter of the store instructions, and the vector memory
         // path charges per instruction
         if (p.res) {
@@ -290,7 +295,7 @@ __global__ __launch_bounds__(64 * WM * WP) void conv_mfma16(ConvParams p, Tile16
 #pragma unroll
                 for (int ni = 0; ni < NI; ++ni)
                     rv[mi][ni] = __builtin_bit_cast(
-                        f32x4, __builtin_amdgcn_raw_buffer_load_b128(rr, ooff[ni], (oc0 + mi * 16) * HWo * 4, 0));
+                        f32x4, __builtin_amdgcn_raw_buffer_load_b128(rr, ooff[ni] | om[mi], (oc0 + mi * 16) * HWo * 4, 0));
 #pragma unroll
             for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
@@ -310,11 +315,12 @@ __global__ __launch_bounds__(64 * WM * WP) void conv_mfma16(ConvParams p, Tile16
         for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
             for (int ni = 0; ni < NI; ++ni)
-                __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, acc[mi][ni]), ry, ooff[ni],
+                __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, acc[mi][ni]), ry, ooff[ni] | om[mi],
                                                        (oc0 + mi * 16) * HWo * 4, 0);
         GSPC_STAMP(6)
         return;
     }
+    const unsigned ocl = oc0 + 4 * (lane >> 4);   // this lane's filter for mi = 0, r = 0
     if (p.res) {
         const __amdgpu_buffer_rsrc_t rr = make_rsrc(p.res, t.y_bytes);
 #pragma unroll
@@ -323,8 +329,8 @@ __global__ __launch_bounds__(64 * WM * WP) void conv_mfma16(ConvParams p, Tile16
             for (int ni = 0; ni < NI; ++ni)
 #pragma unroll
                 for (int r = 0; r < 4; ++r)
-                    acc[mi][ni][r] += __uint_as_float(
-                        __builtin_amdgcn_raw_buffer_load_b32(rr, ooff[ni], (oc0 + mi * 16 + r) * HWo * 4, 0));
+                    acc[mi][ni][r] += __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(
+                        rr, ocl + mi * 16 + r < (unsigned)p.KPG ? ooff[ni] : kOob, (oc0 + mi * 16 + r) * HWo * 4, 0));
     }
 #pragma unroll
     for (int mi = 0; mi < MI; ++mi)
@@ -334,7 +340,8 @@ __global__ __launch_bounds__(64 * WM * WP) void conv_mfma16(ConvParams p, Tile16
             for (int r = 0; r < 4; ++r) {
                 float v = acc[mi][ni][r];
                 if (p.relu) v = fmaxf(v, 0.f);
-                __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(v), ry, ooff[ni],
+                __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(v), ry,
+                                                      ocl + mi * 16 + r < (unsigned)p.KPG ? ooff[ni] : kOob,
                                                       (oc0 + mi * 16 + r) * HWo * 4, 0);
             }
     GSPC_STAMP(6)
@@ -394,7 +401,7 @@ int bank_cost(const ConvParams &p, const Tile16 &t, int plane) {
 
 bool plan16_cfg(const ConvParams &p, const PackGeom &g, const Cfg16 &c, Tile16 *out, int lds_budget = kLdsBudget16) {
     const int MB = 16 * c.MI * c.WM, PB = 16 * c.NI * (c.ksplit ? 1 : c.WP), NT = 64 * c.WM * c.WP;
-    if (g.KPG % MB) return false;
+    if ((g.mtiles * 16) % MB) return false;   // whole filter tiles only; the last tile may be partly padding
     Tile16 t{};
     t.ksplit = c.ksplit;
     if (!split_pixels(p, PB, &t.NB, &t.TH)) return false;
@@ -427,7 +434,7 @@ bool plan16_cfg(const ConvParams &p, const PackGeom &g, const Cfg16 &c, Tile16 *
     t.mtiles = g.mtiles;
     t.row_blocks = (p.Hout + t.TH - 1) / t.TH;
     t.img_blocks = (p.N + t.NB - 1) / t.NB;
-    t.oc_blocks = g.KPG / MB;
+    t.oc_blocks = g.mtiles * 16 / MB;
     const bool check_c = g.CPGp != g.CPG;   // padded channels are masked in the plan: one chunk only
     const int cblks = g.CPGp / 4, taps = p.KH * p.KW;
     int best = 0;
@@ -474,7 +481,7 @@ bool plan16_cfg(const ConvParams &p, const PackGeom &g, const Cfg16 &c, Tile16 *
 // Picks the block shape: the largest one that still gives every CU two blocks,
 // else the one with the most blocks.
 bool plan16(const ConvParams &p, const PackGeom &g, int *cfg_idx, Tile16 *t_out) {
-    if (g.variant != kMfma16 || !p.wm || !shape_instantiated(p.KH, p.KW, p.stride)) return false;
+    if (!g.mfma_bytes || !p.wm || !shape_instantiated(p.KH, p.KW, p.stride)) return false;
     static const char *force = std::getenv("GSPC_TILE16");
     const int forced = force ? std::atoi(force) : tuned_config(p, 'm');
     if (forced >= 0) {
@@ -664,6 +671,8 @@ const Plan &get_plan(const ConvParams &p, const PackGeom &g) {
     if (plan_mfma_bf16(p, g, &pl.pb)) pl.kind = 32;
     else if (fam == 'm' && plan16(p, g, &pl.idx, &pl.t16)) pl.kind = 16;
     else if (plan_mfma16w(p, g, &pl.pw)) pl.kind = 17;
+    // few filters per group: the 4x4x1 kernel where it has an instance, else padded 16-filter tiles
+    else if (g.variant == kMfma4 && fam != 'm' && plan_mfma4(p, g, &pl.p4)) pl.kind = 4;
     else if (plan16(p, g, &pl.idx, &pl.t16)) pl.kind = 16;
     else if (plan_mfma4(p, g, &pl.p4)) pl.kind = 4;
     return cache.emplace(k, pl).first->second;

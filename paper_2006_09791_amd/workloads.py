@@ -158,46 +158,62 @@ class Chain:
                                                  self.weight_groups))]
 
 
-def _basic_stage(ch, cur, N, cin, cout, hw, blocks, g, entry_stride):
+def _conv3(ch, src, dst, tmp, N, cin, hw, cout, stride, g, pointwise, relu, residual=-1):
+    """One 3x3 convolution of a basic block.  pointwise = False: a grouped 3x3 cin -> cout.
+    pointwise = True: the replacement the paper trains (Section IV-A), a grouped 3x3
+    cin -> cin into `tmp` followed by a 1x1 cin -> cout that mixes the groups; the block's
+    ReLU and residual go on the 1x1."""
+    if not pointwise:
+        return ch.conv(src, dst, N, cin, hw, hw, cout, 3, stride, 1, g, relu=relu, residual=residual)[0]
+    ho, _ = ch.conv(src, tmp, N, cin, hw, hw, cin, 3, stride, 1, g)
+    ch.conv(tmp, dst, N, cin, ho, ho, cout, 1, 1, 0, 1, relu=relu, residual=residual)
+    return ho
+
+
+def _basic_stage(ch, cur, N, cin, cout, hw, blocks, g, entry_stride, pointwise=False):
     """Residual stage of basic blocks (two grouped 3x3 convs each).  Buffers
-    1..4 rotate; `cur` holds the stage input.  Returns (buffer, spatial)."""
+    1..4 rotate (5 is the grouped result in the pointwise form); `cur` holds the
+    stage input.  Returns (buffer, spatial)."""
     for b in range(blocks):
         free = [i for i in (1, 2, 3, 4) if i != cur]
         t, sc, out = free[0], free[1], free[2]
         if b == 0 and (entry_stride != 1 or cin != cout):
             ho, _ = ch.conv(cur, sc, N, cin, hw, hw, cout, 1, entry_stride, 0, 1)
-            ch.conv(cur, t, N, cin, hw, hw, cout, 3, entry_stride, 1, g, relu=True)
-            ch.conv(t, out, N, cout, ho, ho, cout, 3, 1, 1, g, relu=True, residual=sc)
+            _conv3(ch, cur, t, 5, N, cin, hw, cout, entry_stride, g, pointwise, True)
+            _conv3(ch, t, out, 5, N, cout, ho, cout, 1, g, pointwise, True, residual=sc)
             hw = ho
         else:
-            ch.conv(cur, t, N, cout, hw, hw, cout, 3, 1, 1, g, relu=True)
-            ch.conv(t, out, N, cout, hw, hw, cout, 3, 1, 1, g, relu=True, residual=cur)
+            _conv3(ch, cur, t, 5, N, cout, hw, cout, 1, g, pointwise, True)
+            _conv3(ch, t, out, 5, N, cout, hw, cout, 1, g, pointwise, True, residual=cur)
         cur = out
     return cur, hw
 
 
-def wrn_chain(N, g):
-    """WRN-40-2-style CIFAR stack, every 3x3 conv after the stem grouped."""
-    ch = Chain(f"wrn40x2_g{g}_n{N}", (N, 3, 32, 32))
+def wrn_chain(N, g, pointwise=False):
+    """WRN-40-2-style CIFAR stack, every 3x3 conv after the stem grouped.  pointwise = True
+    is the form of the paper's trained networks (Section IV-A): each of those convolutions
+    becomes a grouped 3x3 a -> a plus a 1x1 a -> b."""
+    ch = Chain(f"wrn40x2{'pw' if pointwise else ''}_g{g}_n{N}", (N, 3, 32, 32))
     ch.conv(0, 1, N, 3, 32, 32, 32, 3, 1, 1, 1, relu=True)
     cur, hw = 1, 32
-    cur, hw = _basic_stage(ch, cur, N, 32, 32, hw, 6, g, 1)
-    cur, hw = _basic_stage(ch, cur, N, 32, 64, hw, 6, g, 2)
-    cur, hw = _basic_stage(ch, cur, N, 64, 128, hw, 6, g, 2)
+    cur, hw = _basic_stage(ch, cur, N, 32, 32, hw, 6, g, 1, pointwise)
+    cur, hw = _basic_stage(ch, cur, N, 32, 64, hw, 6, g, 2, pointwise)
+    cur, hw = _basic_stage(ch, cur, N, 64, 128, hw, 6, g, 2, pointwise)
     return ch
 
 
-def resnet34_chain(N, g):
+def resnet34_chain(N, g, pointwise=False):
     """ResNet-34-shaped ImageNet stack: 7x7 s2 stem, 3x3 s2 max pool, then
-    3/4/6/3 basic blocks with every 3x3 conv grouped."""
-    ch = Chain(f"resnet34_g{g}_n{N}", (N, 3, 224, 224))
+    3/4/6/3 basic blocks with every 3x3 conv grouped (pointwise = True: each followed
+    by a 1x1, as in wrn_chain)."""
+    ch = Chain(f"resnet34{'pw' if pointwise else ''}_g{g}_n{N}", (N, 3, 224, 224))
     ho, _ = ch.conv(0, 1, N, 3, 224, 224, 64, 7, 2, 3, 1, relu=True)
     ho, _ = ch.maxpool(1, 2, N, 64, ho, ho)
     cur, hw = 2, ho
-    cur, hw = _basic_stage(ch, cur, N, 64, 64, hw, 3, g, 1)
-    cur, hw = _basic_stage(ch, cur, N, 64, 128, hw, 4, g, 2)
-    cur, hw = _basic_stage(ch, cur, N, 128, 256, hw, 6, g, 2)
-    cur, hw = _basic_stage(ch, cur, N, 256, 512, hw, 3, g, 2)
+    cur, hw = _basic_stage(ch, cur, N, 64, 64, hw, 3, g, 1, pointwise)
+    cur, hw = _basic_stage(ch, cur, N, 64, 128, hw, 4, g, 2, pointwise)
+    cur, hw = _basic_stage(ch, cur, N, 128, 256, hw, 6, g, 2, pointwise)
+    cur, hw = _basic_stage(ch, cur, N, 256, 512, hw, 3, g, 2, pointwise)
     return ch
 
 
@@ -222,6 +238,40 @@ def mobilenet_chain(N, g=None, hw=224):
         ho, _ = ch.conv(cur, mid, N, a, h, h, a, 3, s, 1, a if g is None else g, relu=True)
         ch.conv(mid, out, N, a, ho, ho, b_, 1, 1, 0, 1, relu=True)
         cur, h = out, ho
+    return ch
+
+
+# (expansion t, channels out, repeats, stride of the first repeat) of the bottleneck stages of the
+# MobileNetV2 ImageNet definition (its architecture table), between a 3x3 stride-2 stem 3 -> 32 and
+# a final 1x1 320 -> 1280
+MOBILENETV2_STAGES = [(1, 16, 1, 1), (6, 24, 2, 2), (6, 32, 3, 2), (6, 64, 4, 2), (6, 96, 3, 1),
+                      (6, 160, 3, 2), (6, 320, 1, 1)]
+
+
+def mobilenetv2_chain(N, g=None, hw=224):
+    """MobileNetV2-shaped stack (Section IV-A's third network): inverted-residual blocks of a
+    1x1 expansion a -> t*a, a 3x3 convolution t*a -> t*a with g groups (g = None: the depthwise
+    original, G(N)) and a linear 1x1 projection t*a -> b, with the block input added where
+    stride 1 keeps the shape.  The activation is the chain's ReLU (the original clips at 6;
+    the shapes, not the clip, are what is timed).  Buffers 1..4 rotate."""
+    tag = "dw" if g is None else f"g{g}"
+    ch = Chain(f"mobilenetv2_{tag}_n{N}", (N, 3, hw, hw))
+    h, _ = ch.conv(0, 1, N, 3, hw, hw, 32, 3, 2, 1, 1, relu=True)
+    cur, a = 1, 32
+    for t, c, n, s in MOBILENETV2_STAGES:
+        for i in range(n):
+            stride = s if i == 0 else 1
+            e, d, out = [k for k in (1, 2, 3, 4) if k != cur][:3]
+            m = a * t
+            src = cur
+            if t != 1:
+                ch.conv(cur, e, N, a, h, h, m, 1, 1, 0, 1, relu=True)
+                src = e
+            ho, _ = ch.conv(src, d, N, m, h, h, m, 3, stride, 1, m if g is None else g, relu=True)
+            ch.conv(d, out, N, m, ho, ho, c, 1, 1, 0, 1, residual=cur if (stride == 1 and a == c) else -1)
+            cur, a, h = out, c, ho
+    e = 1 if cur != 1 else 2
+    ch.conv(cur, e, N, a, h, h, 1280, 1, 1, 0, 1, relu=True)
     return ch
 
 

@@ -124,3 +124,40 @@ def test_autotuner_table_lines_parse_back():
     assert autotune.table_line(s, "bf16", "b", 0).split()[10] == "1"
     shapes, dtype = autotune.workload_shapes("resnet34_bf16", 256)
     assert dtype == "bf16" and len(shapes) == 21
+
+
+def test_mobilenetv2_shaped_chain_matches_the_published_model_size():
+    """Section IV-A quotes 3.5 million parameters and 53 layers for MobileNetV2: the chain's
+    52 convolutions carry 2.19 M weights, which with the 1280 -> 1000 classifier (1.281 M) and
+    the 34 112 batch-norm scales and shifts (two per output channel of every convolution)
+    give that figure; the depthwise form needs about 300 M multiply-accumulates (Eq. 2 summed)."""
+    import numpy as np
+    from paper_2006_09791_amd import workloads as wl
+    ch = wl.mobilenetv2_chain(1)
+    assert len(ch.layers) == 52 and all(l.op == "conv" for l in ch.layers)
+    weights = sum(int(np.prod(s)) for s in ch.weight_shapes)
+    bn = 2 * sum(s[0] for s in ch.weight_shapes)
+    assert weights == 2189760 and bn == 34112
+    assert abs(weights + bn + 1280 * 1000 + 1000 - 3.5e6) < 0.01 * 3.5e6
+    assert abs(ch.macs() - 300e6) < 0.01 * 300e6
+    assert ch.out_shape == (1, 1280, 7, 7)
+    # G(g) variants keep every shape and scale the 3x3 work by channels / g
+    for g in (2, 4, 8, 16):
+        cg = wl.mobilenetv2_chain(1, g)
+        assert [(l.Cin, l.Cout, l.H, l.KH, l.stride) for l in cg.layers] == [(l.Cin, l.Cout, l.H, l.KH, l.stride) for l in ch.layers]
+        assert all(l.groups in (1, g) for l in cg.layers)
+    # no step reads a buffer it writes
+    for l in ch.layers:
+        assert l.dst != l.src and l.dst != l.src2
+
+
+def test_pointwise_form_doubles_the_3x3_layers():
+    """Section IV-A: each 3x3 convolution becomes a grouped 3x3 a -> a plus a 1x1 a -> b."""
+    from paper_2006_09791_amd import workloads as wl
+    plain, pw = wl.wrn_chain(1, 4), wl.wrn_chain(1, 4, pointwise=True)
+    n3 = sum(1 for l in plain.layers[1:] if l.KH == 3)
+    assert len(pw.layers) == len(plain.layers) + n3
+    for l in pw.layers[1:]:
+        if l.KH == 3:
+            assert l.Cin == l.Cout and l.groups == 4
+    assert pw.out_shape == plain.out_shape

@@ -158,3 +158,59 @@ def test_mobilenet_chain(N, g):
     got, ref = _run(chain, 5, wl.make_seed(5, N, 0 if g is None else g))
     assert np.abs(ref).max() > 0
     assert rel_err(got, ref) < TOL_F32
+
+
+@pytest.mark.parametrize("N,g", [(1, None), (1, 8), (3, None), (2, 16)], ids=["n1-depthwise", "n1-g8", "n3-depthwise", "n2-g16"])
+def test_mobilenetv2_chain(N, g):
+    """MobileNetV2-shaped stack (Section IV-A): inverted-residual blocks with the 3x3
+    convolution depthwise (the original, G(N)) or with g groups; 52 convolutions with
+    residual additions on the linear projections."""
+    chain = wl.mobilenetv2_chain(N, g, hw=224 if N == 1 else 96)
+    got, ref = _run(chain, 6, wl.make_seed(6, N, 0 if g is None else g))
+    assert np.abs(ref).max() > 0
+    assert rel_err(got, ref) < TOL_F32
+
+
+@pytest.mark.parametrize("net,N,g", [("wrn", 1, 2), ("wrn", 2, 4), ("wrn", 1, 16), ("resnet34", 1, 8)])
+def test_pointwise_form_chain(net, N, g):
+    """The form of the paper's trained networks (Section IV-A): every 3x3 convolution of
+    a basic block replaced by a grouped 3x3 a -> a followed by a pointwise a -> b."""
+    chain = wl.wrn_chain(N, g, pointwise=True) if net == "wrn" else wl.resnet34_chain(N, g, pointwise=True)
+    got, ref = _run(chain, 7, wl.make_seed(7, N, g))
+    assert np.abs(ref).max() > 0
+    assert rel_err(got, ref) < TOL_F32
+
+
+@pytest.mark.parametrize("s", [
+    wl.ConvShape(3, 96, 7, 7, 40, 1, 1, 1, 0, 1),      # 40 filters, 49-element planes: 4-byte stores
+    wl.ConvShape(2, 144, 12, 12, 144, 3, 3, 1, 1, 8),  # 18 filters per group: 16-byte stores
+    wl.ConvShape(2, 120, 10, 10, 120, 3, 3, 2, 1, 2),  # 60 filters per group, stride 2, 25-element planes
+], ids=lambda s: "x".join(map(str, s)))
+def test_padded_filter_tile_with_residual_and_relu(s):
+    """Residual operand and ReLU on a layer whose last filter tile is partly padding: the
+    padding filters must neither read nor write (the buffers end right after the tensor)."""
+    import torch
+    import oracle
+    from paper_2006_09791_amd import binding as b
+    dev = torch.device("cuda:0")
+    b.gspc_set_stream()
+    x = wl.make_input((s.N, s.Cin, s.H, s.W), 51)
+    w = wl.make_weight(s.Cout, s.Cin // s.groups, s.KH, s.KW, 52)
+    ho, wo = b.gspc_output_dims(s.H, s.W, s.KH, s.KW, s.stride, s.pad)
+    res = wl.make_input((s.N, s.Cout, ho, wo), 53)
+    pw = b.gspc_pack_weights(torch.from_numpy(w).to(dev), s.groups)
+    xd = torch.from_numpy(x).to(dev).reshape(-1)
+    rd = torch.from_numpy(res).to(dev).reshape(-1)
+    # the output sits in the middle of a NaN-filled buffer: nothing around it may change
+    guard = 4096
+    yd = torch.full((res.size + 2 * guard,), float("nan"), dtype=torch.float32, device=dev)
+    layer = wl.Layer("conv", 0, 1, 2, s.N, s.Cin, s.H, s.W, s.Cout, s.KH, s.KW, s.stride, s.pad, s.groups, True, 0)
+    lc = b.LayerChain([layer], [pw], [xd, rd, yd[guard:guard + res.size]])
+    b.gspc_run_layer_chain(lc)
+    torch.cuda.synchronize()
+    assert b.gspc_last_kernel().startswith("conv_mfma16<"), b.gspc_last_kernel()
+    out = yd.cpu().numpy()
+    assert np.isnan(out[:guard]).all() and np.isnan(out[guard + res.size:]).all()
+    got = out[guard:guard + res.size].reshape(res.shape)
+    ref = oracle.relu(oracle.add(oracle.conv2d_grouped(x, w, s.stride, s.pad, s.groups, threads=8), res))
+    assert rel_err(got, ref) < TOL_F32

@@ -247,3 +247,30 @@ def test_tile_table_overrides_the_planner(gpu, tmp_path):
     lines = [l for l in out.strip().splitlines() if l.startswith("conv_")]
     assert lines[0].startswith("conv_mfma16<1,1,1,4,3,3,1,f32,") and lines[0].endswith("True"), out
     assert lines[1].startswith("conv_mfma16w<") and lines[1].endswith("True"), out
+
+
+# Filters per group that are not a multiple of 16 (the G(g) forms of a MobileNetV2-shaped
+# network, Section IV-A: 96, 144, 192, 384, 576 and 960 channels over 2..16 groups): the plain
+# 16x16x4 kernel zero-pads the last filter tile and drops its padding filters at the store.
+PADDED_TILES = [
+    S(2, 960, 7, 7, 960, 3, 3, 1, 1, 8),     # 120 filters: 8 tiles, the last half empty; scalar stores
+    S(1, 144, 28, 28, 144, 3, 3, 1, 1, 2),   # 72: 5 tiles; 16-byte stores
+    S(3, 144, 28, 28, 144, 3, 3, 2, 1, 2),   # stride 2
+    S(2, 240, 14, 14, 240, 3, 3, 1, 1, 4),   # 60
+    S(2, 144, 20, 20, 144, 3, 3, 1, 1, 4),   # 36
+    S(1, 96, 56, 56, 96, 3, 3, 2, 1, 4),     # 24
+    S(2, 144, 14, 14, 144, 3, 3, 1, 1, 8),   # 18 filters and 18 channels: both edges padded
+    S(2, 192, 28, 28, 192, 3, 3, 2, 1, 16),  # 12
+    S(3, 144, 12, 12, 144, 3, 3, 1, 1, 16),  # 9
+    S(2, 96, 16, 16, 96, 3, 3, 2, 1, 16),    # 6
+    S(2, 20, 9, 9, 20, 3, 3, 1, 1, 4),       # 5, odd plane
+    S(2, 144, 28, 28, 24, 1, 1, 1, 0, 1),    # pointwise projection to 24 channels
+    S(3, 96, 7, 7, 40, 1, 1, 1, 0, 1),       # pointwise, 49-element planes
+    S(70, 144, 14, 14, 144, 3, 3, 1, 1, 2),  # 72 at a batch that fills the chip (larger block shapes)
+]
+
+
+@pytest.mark.parametrize("s", PADDED_TILES, ids=lambda s: "x".join(map(str, s)))
+def test_filters_per_group_not_a_multiple_of_16(gpu, s):
+    name = check(gpu, s, seed=23)
+    assert name.startswith("conv_mfma16<"), name
