@@ -29,7 +29,7 @@ namespace gspc {
 // chunks of CK channels; chunk i+1 is fetched from global memory into
 // registers while chunk i is multiplied out of LDS (two LDS buffers).
 // ---------------------------------------------------------------------------
-constexpr int kTmax16 = 4, kWmax16 = 4;
+constexpr int kTmax16 = 4, kTmax16Stem = 10, kWmax16 = 4;
 
 struct Tile16 {
     int NB, TH, IHt;         // images, output rows per block; staged input rows
@@ -62,7 +62,8 @@ template <int MI, int NI, int WM, int WP, int KH, int KW, int S, typename TIN, b
 __global__ __launch_bounds__(64 * WM * WP) void conv_mfma16(ConvParams p, Tile16 t) {
     GSPC_STAMP(0)
     constexpr int NT = 64 * WM * WP, TAPS = KH * KW, MIWM = MI * WM;
-    constexpr int TMAX = kTmax16, WMAX = kWmax16, ES = (int)sizeof(TIN);
+    // (the 7x7 stem stages nine 224-pixel rows per 4-channel block: more rows per thread)
+    constexpr int TMAX = KH == 7 ? kTmax16Stem : kTmax16, WMAX = kWmax16, ES = (int)sizeof(TIN);
     extern __shared__ f32x4 smem4[];
     float *smem = reinterpret_cast<float *>(smem4);
     const int buf_floats = t.in_floats + t.w_floats + 4;
@@ -444,7 +445,7 @@ bool plan16_cfg(const ConvParams &p, const PackGeom &g, const Cfg16 &c, Tile16 *
         const int wsl = (c.MI * c.WM * d * taps * 16 + NT - 1) / NT;
         const size_t in_f = (size_t)CK * t.PLANE, w_f = (size_t)wsl * NT * 4;
         if (2 * (in_f + w_f + 4) * sizeof(float) > (size_t)(c.ksplit ? 2 * lds_budget : lds_budget)) continue;
-        if ((CK * t.NB * t.IHt + rpp - 1) / rpp > kTmax16) continue;
+        if ((CK * t.NB * t.IHt + rpp - 1) / rpp > (p.KH == 7 ? kTmax16Stem : kTmax16)) continue;
         if (wsl > kWmax16) continue;
         best = d;
     }
