@@ -24,7 +24,7 @@ EXPORTS = [
     "gspc_version", "gspc_set_stream", "gspc_last_error", "gspc_output_dims", "gspc_layer_macs",
     "gspc_packed_weight_bytes", "gspc_pack_weights", "gspc_unpack_weights", "gspc_packed_free",
     "gspc_packed_info", "gspc_pack_input_bf16", "gspc_conv2d_grouped", "gspc_force_path",
-    "gspc_last_path", "gspc_last_kernel", "gspc_set_graph_mode", "gspc_set_chain_fusion", "gspc_run_layer_chain",
+    "gspc_last_path", "gspc_last_kernel", "gspc_set_graph_mode", "gspc_set_chain_fusion", "gspc_set_winograd", "gspc_run_layer_chain",
 ]
 
 
@@ -90,6 +90,8 @@ def load():
     lib.gspc_set_graph_mode.argtypes = [i]
     lib.gspc_set_chain_fusion.restype = i
     lib.gspc_set_chain_fusion.argtypes = [i]
+    lib.gspc_set_winograd.restype = i
+    lib.gspc_set_winograd.argtypes = [i]
     lib.gspc_last_kernel.restype = ctypes.c_char_p
     lib.gspc_run_layer_chain.restype = i
     lib.gspc_run_layer_chain.argtypes = [ctypes.POINTER(GspcLayer), i, ctypes.POINTER(vp),
@@ -221,6 +223,10 @@ def gspc_set_graph_mode(on):
 
 def gspc_set_chain_fusion(on):
     _check(load().gspc_set_chain_fusion(1 if on else 0))
+
+
+def gspc_set_winograd(on):
+    _check(load().gspc_set_winograd(1 if on else 0))
 
 
 def gspc_last_path():

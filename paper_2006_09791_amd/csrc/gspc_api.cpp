@@ -21,6 +21,7 @@ thread_local int t_last_path = GSPC_PATH_AUTO;
 thread_local const char *t_last_kernel = "";
 thread_local int t_graph_mode = 1;
 thread_local int t_fusion = 1;
+thread_local int t_winograd = 0;
 
 // Recorded layer chains, per thread, keyed by everything a replay depends on.
 struct ChainGraph {
@@ -129,6 +130,9 @@ int prepare_conv(const void *input, const gspc_packed_t *pw, int N, int Cin, int
                                                   pw->geom.mfma_offset)
                 : nullptr;
     p->wb = pw->geom.bf16_bytes ? static_cast<const char *>(pw->dev) + pw->geom.bf16_offset : nullptr;
+    p->wx = pw->geom.wino_bytes
+                ? reinterpret_cast<const float *>(static_cast<const char *>(pw->dev) + pw->geom.wino_offset)
+                : nullptr;
     p->y = static_cast<float *>(output);
     p->res = nullptr;
     p->N = N; p->Cin = Cin; p->H = H; p->W = W; p->Cout = Cout; p->KH = KH; p->KW = KW;
@@ -184,6 +188,11 @@ int dispatch_conv(const gspc::ConvParams &p, const gspc_packed_t *pw) {
 
 namespace gspc {
 
+bool winograd_enabled() {
+    static const bool env = std::getenv("GSPC_WINOGRAD") != nullptr;
+    return t_winograd != 0 || env;
+}
+
 PackGeom make_pack_geom(int Cin, int Cout, int KH, int KW, int groups, int dtype) {
     PackGeom g{};
     g.CPG = Cin / groups;
@@ -214,6 +223,11 @@ PackGeom make_pack_geom(int Cin, int Cout, int KH, int KW, int groups, int dtype
         g.bf16_bytes = (size_t)groups * g.nchunks_b * g.ks_b * g.mtiles_b * 1024;
     }
     g.total_bytes = g.bf16_bytes ? g.bf16_offset + g.bf16_bytes : g.mfma_offset + g.mfma_bytes;
+    if (dtype == GSPC_F32 && KH == 3 && KW == 3 && g.KPG % 16 == 0 && g.CPG % 4 == 0 && g.CPG >= 8) {
+        g.wino_offset = (g.total_bytes + 255) / 256 * 256;
+        g.wino_bytes = (size_t)groups * (g.CPG / 4) * (g.KPG / 16) * 4096;
+        g.total_bytes = g.wino_offset + g.wino_bytes;
+    }
     return g;
 }
 
@@ -356,6 +370,11 @@ int gspc_set_graph_mode(int on) {
 
 int gspc_set_chain_fusion(int on) {
     t_fusion = on ? 1 : 0;
+    return GSPC_OK;
+}
+
+int gspc_set_winograd(int on) {
+    t_winograd = on ? 1 : 0;
     return GSPC_OK;
 }
 
@@ -515,7 +534,7 @@ int gspc_run_layer_chain(const gspc_layer_t *layers, int n_layers, void *const *
                                hipStreamIsCapturing(t_stream, &cap) == hipSuccess &&
                                cap == hipStreamCaptureStatusNone;
         if (try_graph) {
-            const uint64_t key = chain_key(layers, n_layers, act_bufs, n_bufs, t_stream, t_force_path, t_fusion);
+            const uint64_t key = chain_key(layers, n_layers, act_bufs, n_bufs, t_stream, t_force_path, t_fusion + 2 * t_winograd);
             auto it = t_graphs.find(key);
             if (it == t_graphs.end()) {
                 hipGraph_t graph = nullptr;

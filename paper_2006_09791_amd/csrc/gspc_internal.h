@@ -47,6 +47,11 @@ struct PackGeom {
     // unit 4*s + l/16 of filter l%16 (zeros past the last unit).
     int ckb, ks_b, nchunks_b, mtiles_b;
     size_t bf16_bytes, bf16_offset;
+    // Winograd F(2x2, 3x3) section (GSPC_F32 handles, 3x3, KPG % 16 == 0, CPG % 4 == 0,
+    // CPG >= 8): fp32 U = G g G^T as [g][CPG/4][KPG/16][4][64 lanes][4]; lane l holds
+    // filter l % 16 of its tile at channel 4*cblk + l / 16, and its four values in
+    // quad q are the transformed-domain positions 4*q .. 4*q + 3 (position = 4*xi + nu).
+    size_t wino_bytes, wino_offset;
 };
 
 PackGeom make_pack_geom(int Cin, int Cout, int KH, int KW, int groups, int dtype);
@@ -70,6 +75,7 @@ struct ConvParams {
     const float *wd;    // direct section
     const float *wm;    // mfma section (nullptr if none)
     const void *wb;     // bf16 mfma section (nullptr if none)
+    const float *wx;    // Winograd section (nullptr if none)
     float *y;           // [N][Cout][Hout][Wout]
     const float *res;   // optional residual, same shape as y
     int N, Cin, H, W, Cout, KH, KW, stride, pad, groups;
@@ -107,6 +113,16 @@ struct Mfma16wPlan {
 };
 bool plan_mfma16w(const ConvParams &p, const PackGeom &g, Mfma16wPlan *out);
 hipError_t launch_mfma16w(const ConvParams &p, const Mfma16wPlan &plan, hipStream_t s, const char **name);
+
+// Winograd F(2x2, 3x3) on the 16x16x4 MFMA (wino_kernels.hip); used only where asked for
+// (gspc_set_winograd, or family 'x' of the tile table).
+struct WinoPlan {
+    int inst, ckb;
+    int data[48];
+};
+bool plan_wino(const ConvParams &p, const PackGeom &g, WinoPlan *out);
+hipError_t launch_wino(const ConvParams &p, const WinoPlan &plan, hipStream_t s, const char **name);
+bool winograd_enabled();
 
 // 4x4x1 MFMA kernel (weights held in registers); plan is opaque to the caller.
 struct Mfma4Plan {

@@ -642,7 +642,7 @@ hipError_t launch16_cfg(int i, const ConvParams &p, const Tile16 &t, hipStream_t
 // Planning costs microseconds of host time, so its outcome is remembered per
 // thread, keyed by everything it depends on.
 struct PlanKey {
-    int v[14];
+    int v[15];
     bool operator==(const PlanKey &o) const { return std::memcmp(v, o.v, sizeof(v)) == 0; }
 };
 struct PlanKeyHash {
@@ -653,23 +653,25 @@ struct PlanKeyHash {
     }
 };
 struct Plan {
-    int kind;  // 0 none, 32 (bf16), 17 (resident filters), 16, 4
+    int kind;  // 0 none, 32 (bf16), 64 (Winograd), 17 (resident filters), 16, 4
     int idx;
     Tile16 t16;
     Mfma4Plan p4;
     MfmaB16Plan pb;
     Mfma16wPlan pw;
+    WinoPlan px;
 };
 
 const Plan &get_plan(const ConvParams &p, const PackGeom &g) {
     thread_local std::unordered_map<PlanKey, Plan, PlanKeyHash> cache;
     PlanKey k{{p.N, p.Cin, p.H, p.W, p.Cout, p.KH, p.KW, p.stride, p.pad, p.groups, p.in_bf16,
-               g.variant, p.wm != nullptr, p.wb != nullptr}};
+               g.variant, p.wm != nullptr, p.wb != nullptr, winograd_enabled()}};
     auto it = cache.find(k);
     if (it != cache.end()) return it->second;
     Plan pl{};
     const char fam = tuned_family(p);   // offline tile table: may prefer the plain 16x16x4 kernel
     if (plan_mfma_bf16(p, g, &pl.pb)) pl.kind = 32;
+    else if ((winograd_enabled() || fam == 'x') && plan_wino(p, g, &pl.px)) pl.kind = 64;
     else if (fam == 'm' && plan16(p, g, &pl.idx, &pl.t16)) pl.kind = 16;
     else if (plan_mfma16w(p, g, &pl.pw)) pl.kind = 17;
     // few filters per group: the 4x4x1 kernel where it has an instance, else padded 16-filter tiles
@@ -695,6 +697,7 @@ hipError_t launch_mfma(const ConvParams &p, const PackGeom &g, hipStream_t s, co
         return p.in_bf16 ? launch16_cfg<uint16_t>(pl.idx, p, pl.t16, s) : launch16_cfg<float>(pl.idx, p, pl.t16, s);
     }
     if (pl.kind == 32) return launch_mfma_bf16(p, g, pl.pb, s, name);
+    if (pl.kind == 64) return launch_wino(p, pl.px, s, name);
     if (pl.kind == 17) return launch_mfma16w(p, pl.pw, s, name);
     if (pl.kind == 4) return launch_mfma4(p, pl.p4, s, name);
     return hipErrorNotSupported;

@@ -62,6 +62,35 @@ __global__ void pack_mfma_kernel(const float *__restrict__ w, float *__restrict_
     out[d] = v;
 }
 
+// Winograd section: U = G g G^T of every 3x3 filter slice (G of F(2x2, 3x3): rows (1, 0, 0),
+// (1/2, 1/2, 1/2), (1/2, -1/2, 1/2), (0, 0, 1)), one thread per element.
+__global__ void pack_wino_kernel(const float *__restrict__ w, float *__restrict__ out, PackArgs a, size_t total) {
+    size_t d = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (d >= total) return;
+    const int e = (int)(d % 4);
+    size_t r = d / 4;
+    const int lane = (int)(r % 64);
+    r /= 64;
+    const int quad = (int)(r % 4);
+    r /= 4;
+    const int mtiles = a.KPG / 16, cblks = a.CPG / 4;
+    const int mt = (int)(r % mtiles);
+    r /= mtiles;
+    const int cb = (int)(r % cblks);
+    const int j = (int)(r / cblks);
+    const int xi = quad, nu = e;   // position 4*quad + e = 4*xi + nu
+    const int oc = j * a.KPG + mt * 16 + lane % 16, c = cb * 4 + lane / 16;
+    const float *g = w + (size_t)oc * a.Kred + (size_t)c * 9;
+    const float G[4][3] = {{1.f, 0.f, 0.f}, {0.5f, 0.5f, 0.5f}, {0.5f, -0.5f, 0.5f}, {0.f, 0.f, 1.f}};
+    float u = 0.f;
+    for (int p = 0; p < 3; ++p) {
+        float row = 0.f;   // (g G^T)[p][nu]
+        for (int q = 0; q < 3; ++q) row += g[p * 3 + q] * G[nu][q];
+        u += G[xi][p] * row;
+    }
+    out[d] = u;
+}
+
 // bf16 matrix-core section, one thread per 2-byte element.
 __global__ void pack_bf16_kernel(const float *__restrict__ w, uint16_t *__restrict__ out, PackArgs a,
                                  int ckb, int ks_b, int nchunks, size_t total) {
@@ -144,6 +173,13 @@ hipError_t launch_pack_weights(const float *w, const gspc_packed *h, hipStream_t
         const size_t nb = h->geom.bf16_bytes / 2;
         hipLaunchKernelGGL(pack_bf16_kernel, dim3(blocks_for(nb, 256)), dim3(256), 0, s, w, bsec, a,
                            h->geom.ckb, h->geom.ks_b, h->geom.nchunks_b, nb);
+        e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    if (h->geom.wino_bytes) {
+        float *xsec = reinterpret_cast<float *>(static_cast<char *>(h->dev) + h->geom.wino_offset);
+        const size_t nx = h->geom.wino_bytes / sizeof(float);
+        hipLaunchKernelGGL(pack_wino_kernel, dim3(blocks_for(nx, 256)), dim3(256), 0, s, w, xsec, a, nx);
         e = hipGetLastError();
         if (e != hipSuccess) return e;
     }

@@ -1,0 +1,99 @@
+"""GPU parity of the Winograd F(2x2, 3x3) path (the grouped Winograd convolution that
+Section VI of the paper names as future work) against the oracle's plain definition of
+the grouped convolution (Eq. 1).  The identity is exact in real arithmetic; in fp32 the
+transforms add a few roundings of magnitude sum |x||w| * 2^-24, far inside the 1e-4 bar
+of the direct path, which is therefore kept."""
+import numpy as np
+import pytest
+
+import oracle
+from helpers import TOL_F32, rel_err
+from paper_2006_09791_amd import workloads as wl
+from test_gpu_parity import gpu, run_conv  # noqa: F401  (fixture)
+
+pytestmark = pytest.mark.gpu
+
+S = wl.ConvShape
+SHAPES = [
+    # N Cin H W Cout KH KW stride pad groups
+    S(2, 32, 32, 32, 32, 3, 3, 1, 1, 1),     # WRN stage 1: 4 tile rows x 16 tile columns per block
+    S(3, 64, 16, 16, 64, 3, 3, 1, 1, 2),     # a whole plane (64 tiles) per block
+    S(5, 128, 8, 8, 128, 3, 3, 1, 1, 4),     # four images per block, batch not a multiple of four
+    S(1, 64, 56, 56, 64, 3, 3, 1, 1, 2),     # ResNet stage: 28 tile columns, ragged row blocks
+    S(2, 32, 14, 14, 48, 3, 3, 1, 1, 1),     # 48 filters: an odd number of 16-filter tiles
+    S(2, 16, 12, 20, 32, 3, 3, 1, 1, 2),     # 8 channels (the minimum) and 16 filters per group
+    S(3, 32, 7, 7, 32, 3, 3, 1, 1, 1),       # odd plane: last tile row and column half outside
+    S(2, 24, 9, 13, 32, 3, 3, 1, 1, 2),      # 12 channels per group (one 4-channel block per chunk), odd plane
+    S(1, 256, 14, 14, 256, 3, 3, 1, 1, 1),   # long reduction: 32 chunks of 8 channels
+    S(70, 32, 32, 32, 32, 3, 3, 1, 1, 2),    # enough blocks for the largest block shape
+    S(1, 16, 6, 132, 32, 3, 3, 1, 1, 2),     # 66 tile columns: wider than the 64-tile shapes (the 128-tile shape or none)
+]
+
+
+@pytest.fixture()
+def winograd(gpu):
+    _, b = gpu
+    b.gspc_set_winograd(1)
+    yield b
+    b.gspc_set_winograd(0)
+
+
+@pytest.mark.parametrize("s", SHAPES, ids=lambda s: "x".join(map(str, s)))
+def test_winograd_matches_the_definition(gpu, winograd, s):
+    y, x, w, name = run_conv(gpu, s, seed=31)
+    assert name.startswith("conv_wino<"), name
+    ref = oracle.conv2d_grouped(x, w, s.stride, s.pad, s.groups, threads=8)
+    assert not np.isnan(y).any(), f"{name}: output not fully written"
+    assert rel_err(y, ref) < TOL_F32, name
+
+
+def test_winograd_leaves_other_layers_alone(gpu, winograd):
+    for s in (S(2, 32, 16, 16, 32, 3, 3, 2, 1, 1), S(2, 32, 16, 16, 32, 1, 1, 1, 0, 1),
+              S(2, 32, 16, 16, 32, 3, 3, 1, 0, 1), S(2, 32, 16, 16, 24, 3, 3, 1, 1, 1)):
+        y, x, w, name = run_conv(gpu, s, seed=32)
+        assert not name.startswith("conv_wino<"), name
+        assert rel_err(y, oracle.conv2d_grouped(x, w, s.stride, s.pad, s.groups, threads=8)) < TOL_F32
+
+
+def test_winograd_is_off_by_default(gpu):
+    _, _, _, name = run_conv(gpu, SHAPES[0], seed=33)
+    assert not name.startswith("conv_wino<"), name
+
+
+@pytest.mark.parametrize("s", [S(3, 32, 16, 16, 32, 3, 3, 1, 1, 2), S(2, 32, 9, 9, 64, 3, 3, 1, 1, 1)],
+                         ids=lambda s: "x".join(map(str, s)))
+def test_winograd_with_residual_and_relu(gpu, winograd, s):
+    torch, b = gpu
+    dev = torch.device("cuda:0")
+    x = wl.make_input((s.N, s.Cin, s.H, s.W), 61)
+    w = wl.make_weight(s.Cout, s.Cin // s.groups, 3, 3, 62)
+    res = wl.make_input((s.N, s.Cout, s.H, s.W), 63)
+    pw = b.gspc_pack_weights(torch.from_numpy(w).to(dev), s.groups)
+    guard = 4096
+    yd = torch.full((res.size + 2 * guard,), float("nan"), dtype=torch.float32, device=dev)
+    layer = wl.Layer("conv", 0, 1, 2, s.N, s.Cin, s.H, s.W, s.Cout, 3, 3, 1, 1, s.groups, True, 0)
+    lc = b.LayerChain([layer], [pw], [torch.from_numpy(x).to(dev).reshape(-1), torch.from_numpy(res).to(dev).reshape(-1),
+                                      yd[guard:guard + res.size]])
+    b.gspc_run_layer_chain(lc)
+    torch.cuda.synchronize()
+    assert b.gspc_last_kernel().startswith("conv_wino<"), b.gspc_last_kernel()
+    out = yd.cpu().numpy()
+    assert np.isnan(out[:guard]).all() and np.isnan(out[guard + res.size:]).all()
+    ref = oracle.relu(oracle.add(oracle.conv2d_grouped(x, w, 1, 1, s.groups, threads=8), res))
+    assert rel_err(out[guard:guard + res.size].reshape(res.shape), ref) < TOL_F32
+
+
+def test_winograd_wrn_chain(gpu, winograd):
+    """A whole WRN-40-2-style stack (g = 2, batch 2) with every eligible layer on the Winograd path."""
+    from helpers import gpu_chain, oracle_chain
+    torch, b = gpu
+    chain = wl.wrn_chain(2, 2)
+    x0 = wl.make_input(chain.input_shape, 71)
+    weights = chain.make_weights(2)
+    lc, bufs = gpu_chain(chain, x0, weights)
+    b.gspc_run_layer_chain(lc)
+    torch.cuda.synchronize()
+    n_out = int(np.prod(chain.out_shape))
+    got = bufs[chain.out_buf][:n_out].cpu().numpy().reshape(chain.out_shape)
+    ref = oracle_chain(chain, x0, weights)[chain.out_buf]
+    assert rel_err(got, ref) < TOL_F32
