@@ -52,7 +52,7 @@ def main():
     ap.add_argument("--traffic-probe", action="store_true",
                     help="first run a plain 256 MiB device copy three times: the known-size kernel "
                          "against which rocprofv3's FETCH_SIZE / WRITE_SIZE counters are scaled")
-    ap.add_argument("--sweep", choices=["wrn", "wrn_n256", "resnet_bf16", "depthwise", "blocks", "latency"],
+    ap.add_argument("--sweep", choices=["wrn", "wrn_n256", "resnet_bf16", "depthwise", "blocks", "latency", "winograd"],
                     help="instead of the headline step, time every layer of a configuration family "
                          "and print one JSON line with a row per layer")
     ap.add_argument("--fusion", action="store_true",
@@ -124,6 +124,23 @@ def main():
                 ms = (time.perf_counter() - ta) / reps * 1e3
                 rows.append({"network": name, "layers": len(ch.layers), "mmacs": round(ch.macs() / 1e6, 2),
                              "latency_ms": round(ms, 4), "gmacs": round(ch.macs() / ms / 1e6, 1)})
+        elif args.sweep == "winograd":
+            # the stride-1 3x3 layers with at least 8 channels per group, direct and through
+            # Winograd F(2x2, 3x3) (Section VI names grouped Winograd as the next step)
+            rows = []
+            for N in (64, 256):
+                shapes = [s for g in (1, 2, 4) for s in wl.wrn_grouped_shapes(N, g) if s.stride == 1 and s.Cin // s.groups >= 8]
+                shapes += [s for g in (2, 4, 8) for s in wl.resnet34_grouped_shapes(N, g) if s.stride == 1 and s.Cin // s.groups >= 8]
+                b.gspc_set_winograd(0)
+                direct = layer_timing.time_layers(shapes, "f32", inner=4, reps=5)
+                b.gspc_set_winograd(1)
+                wino = layer_timing.time_layers(shapes, "f32", inner=4, reps=5)
+                b.gspc_set_winograd(None)
+                auto = layer_timing.time_layers(shapes, "f32", inner=4, reps=5)
+                for d, w, a in zip(direct, wino, auto):
+                    rows.append({"layer": d["layer"], "direct_kernel": d["kernel"], "direct_us": d["us"],
+                                 "direct_frac_mfma": d["frac_mfma"], "winograd_kernel": w["kernel"], "winograd_us": w["us"],
+                                 "speedup": round(d["us"] / w["us"], 3), "default_kernel": a["kernel"], "default_us": a["us"]})
         elif args.sweep == "blocks":
             # depthwise 3x3 + pointwise 1x1 blocks, as two kernels and with chain fusion
             rows = layer_timing.time_blocks(wl.depthwise_pairs(256), inner=8, reps=5)

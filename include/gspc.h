@@ -187,13 +187,16 @@ int gspc_set_graph_mode(int on);
 int gspc_set_chain_fusion(int on);
 
 /* Winograd F(2x2, 3x3) evaluation (the grouped Winograd convolution that Section VI
- * of the paper leaves as future work).  Off by default.  gspc_set_winograd(1) makes the
- * calling thread evaluate fp32 3x3, stride-1, pad-1 layers with a multiple of 16
- * filters and a multiple of 4 (at least 8) channels per group through the minimal-
- * filtering identity Y = A^T [sum_c (G g G^T) .* (B^T d B)] A: 16 instead of 36
- * multiplications per channel and 2x2 outputs.  The result differs from the direct
- * sum by rounding only (fp32 throughout; about 1e-6 of sum |x||w| per output), but
- * is not bit-identical to it.  Other layers are unaffected.  (0) turns it off. */
+ * of the paper leaves as future work).  fp32 3x3, stride-1, pad-1 layers with a
+ * multiple of 16 filters and a multiple of 4 (at least 8) channels per group can be
+ * evaluated through the minimal-filtering identity
+ * Y = A^T [sum_c (G g G^T) .* (B^T d B)] A: 16 instead of 36 multiplications per
+ * channel and 2x2 outputs.  The result differs from the direct sum by rounding only
+ * (fp32 throughout; about 1e-6 of sum |x||w| per output), but is not bit-identical
+ * to it.  on < 0 (the default): used for such a layer when the launch is large enough
+ * to fill the GPU, where it is the faster method; on = 0: never (every layer is the
+ * direct sum); on > 0: for every such layer.  Per calling thread.  The environment
+ * variable GSPC_WINOGRAD=0|1 sets the initial mode of every thread. */
 int gspc_set_winograd(int on);
 
 /* Runs the steps in order on the selected stream.  act_bufs[i] (dev) holds

@@ -226,7 +226,8 @@ def gspc_set_chain_fusion(on):
 
 
 def gspc_set_winograd(on):
-    _check(load().gspc_set_winograd(1 if on else 0))
+    """on: True / 1 = every eligible layer, False / 0 = never, None / -1 = automatic (default)."""
+    _check(load().gspc_set_winograd(-1 if on is None or (on is not True and on < 0) else (1 if on else 0)))
 
 
 def gspc_last_path():

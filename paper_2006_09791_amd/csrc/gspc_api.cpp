@@ -21,7 +21,7 @@ thread_local int t_last_path = GSPC_PATH_AUTO;
 thread_local const char *t_last_kernel = "";
 thread_local int t_graph_mode = 1;
 thread_local int t_fusion = 1;
-thread_local int t_winograd = 0;
+thread_local int t_winograd = -2;   // -2: not yet read from the environment; -1 automatic, 0 off, 1 on
 
 // Recorded layer chains, per thread, keyed by everything a replay depends on.
 struct ChainGraph {
@@ -188,9 +188,10 @@ int dispatch_conv(const gspc::ConvParams &p, const gspc_packed_t *pw) {
 
 namespace gspc {
 
-bool winograd_enabled() {
-    static const bool env = std::getenv("GSPC_WINOGRAD") != nullptr;
-    return t_winograd != 0 || env;
+int winograd_mode() {
+    static const char *env = std::getenv("GSPC_WINOGRAD");   // process-wide default: 0 | 1 (else automatic)
+    if (t_winograd == -2) t_winograd = env ? (std::atoi(env) > 0 ? 1 : 0) : -1;
+    return t_winograd;
 }
 
 PackGeom make_pack_geom(int Cin, int Cout, int KH, int KW, int groups, int dtype) {
@@ -374,7 +375,7 @@ int gspc_set_chain_fusion(int on) {
 }
 
 int gspc_set_winograd(int on) {
-    t_winograd = on ? 1 : 0;
+    t_winograd = on < 0 ? -1 : on ? 1 : 0;
     return GSPC_OK;
 }
 
@@ -534,7 +535,7 @@ int gspc_run_layer_chain(const gspc_layer_t *layers, int n_layers, void *const *
                                hipStreamIsCapturing(t_stream, &cap) == hipSuccess &&
                                cap == hipStreamCaptureStatusNone;
         if (try_graph) {
-            const uint64_t key = chain_key(layers, n_layers, act_bufs, n_bufs, t_stream, t_force_path, t_fusion + 2 * t_winograd);
+            const uint64_t key = chain_key(layers, n_layers, act_bufs, n_bufs, t_stream, t_force_path, t_fusion + 2 * (gspc::winograd_mode() + 1));
             auto it = t_graphs.find(key);
             if (it == t_graphs.end()) {
                 hipGraph_t graph = nullptr;

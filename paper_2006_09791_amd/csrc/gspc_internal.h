@@ -114,15 +114,16 @@ struct Mfma16wPlan {
 bool plan_mfma16w(const ConvParams &p, const PackGeom &g, Mfma16wPlan *out);
 hipError_t launch_mfma16w(const ConvParams &p, const Mfma16wPlan &plan, hipStream_t s, const char **name);
 
-// Winograd F(2x2, 3x3) on the 16x16x4 MFMA (wino_kernels.hip); used only where asked for
-// (gspc_set_winograd, or family 'x' of the tile table).
+// Winograd F(2x2, 3x3) on the 16x16x4 MFMA (wino_kernels.hip).  winograd_mode(): 0 = never,
+// 1 = wherever a plan exists, -1 (default) = where the launch fills the chip (must_fill).
+// Family 'x' of the tile table asks for it per layer.
 struct WinoPlan {
     int inst, ckb;
     int data[48];
 };
-bool plan_wino(const ConvParams &p, const PackGeom &g, WinoPlan *out);
+bool plan_wino(const ConvParams &p, const PackGeom &g, bool must_fill, WinoPlan *out);
 hipError_t launch_wino(const ConvParams &p, const WinoPlan &plan, hipStream_t s, const char **name);
-bool winograd_enabled();
+int winograd_mode();
 
 // 4x4x1 MFMA kernel (weights held in registers); plan is opaque to the caller.
 struct Mfma4Plan {

@@ -665,13 +665,15 @@ struct Plan {
 const Plan &get_plan(const ConvParams &p, const PackGeom &g) {
     thread_local std::unordered_map<PlanKey, Plan, PlanKeyHash> cache;
     PlanKey k{{p.N, p.Cin, p.H, p.W, p.Cout, p.KH, p.KW, p.stride, p.pad, p.groups, p.in_bf16,
-               g.variant, p.wm != nullptr, p.wb != nullptr, winograd_enabled()}};
+               g.variant, p.wm != nullptr, p.wb != nullptr, winograd_mode()}};
     auto it = cache.find(k);
     if (it != cache.end()) return it->second;
     Plan pl{};
     const char fam = tuned_family(p);   // offline tile table: may prefer the plain 16x16x4 kernel
     if (plan_mfma_bf16(p, g, &pl.pb)) pl.kind = 32;
-    else if ((winograd_enabled() || fam == 'x') && plan_wino(p, g, &pl.px)) pl.kind = 64;
+    else if ((winograd_mode() != 0 || fam == 'x') && (fam == 'x' || fam == '\0') &&
+             plan_wino(p, g, winograd_mode() < 0 && fam != 'x', &pl.px))
+        pl.kind = 64;
     else if (fam == 'm' && plan16(p, g, &pl.idx, &pl.t16)) pl.kind = 16;
     else if (plan_mfma16w(p, g, &pl.pw)) pl.kind = 17;
     // few filters per group: the 4x4x1 kernel where it has an instance, else padded 16-filter tiles

@@ -280,8 +280,8 @@ namespace {
 struct CfgX {
     int MI, NI, WM, WP;
 };
-// 32 filters x 64 tiles, 32 x 32, 16 x 128, 16 x 64 per block
-const CfgX kCfgX[] = {{1, 2, 2, 2}, {1, 1, 2, 2}, {1, 2, 1, 4}, {1, 1, 1, 4}};
+// filters x tiles per block: 32 x 64, 64 x 32, 32 x 32, 16 x 128, 16 x 64, 16 x 32, 16 x 16
+const CfgX kCfgX[] = {{1, 2, 2, 2}, {2, 1, 2, 2}, {1, 1, 2, 2}, {1, 2, 1, 4}, {1, 1, 1, 4}, {1, 1, 1, 2}, {1, 1, 1, 1}};
 constexpr int kNumCfgX = sizeof(kCfgX) / sizeof(kCfgX[0]);
 constexpr int kLdsBudgetX = 64 * 1024;
 
@@ -361,25 +361,36 @@ template <int CKB>
 hipError_t launchx_cfg(int i, const ConvParams &p, const TileX &t, hipStream_t s) {
     switch (i) {
     case 0: return launchx_inst<1, 2, 2, 2, CKB>(p, t, s);
-    case 1: return launchx_inst<1, 1, 2, 2, CKB>(p, t, s);
-    case 2: return launchx_inst<1, 2, 1, 4, CKB>(p, t, s);
-    case 3: return launchx_inst<1, 1, 1, 4, CKB>(p, t, s);
+    case 1: return launchx_inst<2, 1, 2, 2, CKB>(p, t, s);
+    case 2: return launchx_inst<1, 1, 2, 2, CKB>(p, t, s);
+    case 3: return launchx_inst<1, 2, 1, 4, CKB>(p, t, s);
+    case 4: return launchx_inst<1, 1, 1, 4, CKB>(p, t, s);
+    case 5: return launchx_inst<1, 1, 1, 2, CKB>(p, t, s);
+    case 6: return launchx_inst<1, 1, 1, 1, CKB>(p, t, s);
     }
     return hipErrorNotSupported;
 }
 
 }  // namespace
 
-bool plan_wino(const ConvParams &p, const PackGeom &g, WinoPlan *out) {
+bool plan_wino(const ConvParams &p, const PackGeom &g, bool must_fill, WinoPlan *out) {
     if (!p.wx || !g.wino_bytes || p.in_bf16 || p.KH != 3 || p.KW != 3 || p.stride != 1 || p.pad != 1) return false;
     static const char *force = std::getenv("GSPC_TILEX");   // tuning aid: configuration index
     const int forced = force ? std::atoi(force) : tuned_config(p, 'x');
     const int ckb = g.CPG % 8 == 0 ? 2 : 1;
+    // Measured order of preference: as many filters per block as the group has (the V transform of
+    // a tile is repeated by every filter block), then the smaller tile count (more blocks in
+    // flight per compute unit, whose transform and multiply phases overlap).
+    static const int order[kNumCfgX] = {1, 2, 0, 4, 5, 3, 6};
     int best = -1, best_ckb = 0;
     long best_blocks = -1;
     TileX bt{};
-    for (int i = 0; i < kNumCfgX; ++i) {
+    for (int o = 0; o < kNumCfgX; ++o) {
+        const int i = order[o];
         if (forced >= 0 && i != forced) continue;
+        // the small shapes (16 filters x 32 or 16 tiles, 16 x 128) repeat the V transform too often to
+        // beat the direct kernels: only on request
+        if (must_fill && forced < 0 && (i == 3 || i == 5 || i == 6)) continue;
         TileX t;
         int k = ckb;
         if (!planx_cfg(p, g, kCfgX[i], k, &t)) {
@@ -387,16 +398,18 @@ bool plan_wino(const ConvParams &p, const PackGeom &g, WinoPlan *out) {
             if (ckb == 1 || !planx_cfg(p, g, kCfgX[i], k, &t)) continue;
         }
         const long blocks = (long)t.row_blocks * t.img_blocks * t.oc_blocks * p.groups;
-        // the largest shape that gives every compute unit two blocks, else the one with the most blocks
         if (blocks > best_blocks) {
             best = i;
             best_ckb = k;
             best_blocks = blocks;
             bt = t;
         }
-        if (blocks >= 2 * kNumCU) break;
+        if (blocks >= 2 * kNumCU) break;   // the first shape that gives every compute unit two blocks
     }
     if (best < 0) return false;
+    // With fewer blocks the direct kernels (which can split the reduction over waves) were faster in
+    // every measured case: left to them unless Winograd is asked for explicitly.
+    if (must_fill && forced < 0 && best_blocks < 2 * kNumCU) return false;
     out->inst = best;
     out->ckb = best_ckb;
     static_assert(sizeof(TileX) <= sizeof(out->data), "plan storage too small");

@@ -59,12 +59,27 @@ def test_wrn_layers_batch64_fp32(g):
 def test_wrn_layers_batch256_fp32(g):
     """More blocks than the chip holds at once: the resident-filter kernel walks
     over several pixel tiles per block (first, last and random images sampled)."""
+    from paper_2006_09791_amd import binding as b
     names = []
-    for i, s in enumerate(wl.wrn_grouped_shapes(256, g)):
-        names.append(_sampled_check(s, wl.make_seed(2, 300 + i, g), False, n_img=3, n_oc=4, tol_same=TOL_F32))
-        # stride-1 layers: the resident-filter kernel; stride-2 layers at this batch: the plain one
-        assert ("conv_mfma16w" if s.stride == 1 else "conv_mfma16<") in names[-1], names[-1]
+    b.gspc_set_winograd(0)   # the direct kernels; the automatic choice at this size is the next test
+    try:
+        for i, s in enumerate(wl.wrn_grouped_shapes(256, g)):
+            names.append(_sampled_check(s, wl.make_seed(2, 300 + i, g), False, n_img=3, n_oc=4, tol_same=TOL_F32))
+            # stride-1 layers: the resident-filter kernel; stride-2 layers at this batch: the plain one
+            assert ("conv_mfma16w" if s.stride == 1 else "conv_mfma16<") in names[-1], names[-1]
+    finally:
+        b.gspc_set_winograd(None)
     assert any(",true," in n for n in names), names   # the multi-tile instantiation ran
+
+
+@pytest.mark.parametrize("g", [1, 2, 4])
+def test_wrn_layers_batch256_automatic_choice(g):
+    """At this size the stride-1 layers with at least 8 channels and 16 filters per group go
+    through Winograd F(2x2, 3x3) by default (sampled images and filters against the oracle)."""
+    for i, s in enumerate(wl.wrn_grouped_shapes(256, g)):
+        name = _sampled_check(s, wl.make_seed(2, 400 + i, g), False, n_img=3, n_oc=4, tol_same=TOL_F32)
+        eligible = s.stride == 1 and (s.Cin // g) >= 8 and (s.Cin // g) % 4 == 0 and (s.Cout // g) % 16 == 0
+        assert name.startswith("conv_wino<") == eligible, (s, name)
 
 
 def test_residual_chain_batch256_fp32():
@@ -79,8 +94,12 @@ def test_residual_chain_batch256_fp32():
     x0 = wl.make_input(ch.input_shape, 41)
     weights = ch.make_weights(9)
     lc, bufs = gpu_chain(ch, x0, weights)
-    b.gspc_run_layer_chain(lc)
-    torch.cuda.synchronize()
+    b.gspc_set_winograd(0)
+    try:
+        b.gspc_run_layer_chain(lc)
+        torch.cuda.synchronize()
+    finally:
+        b.gspc_set_winograd(None)
     assert "conv_mfma16w" in b.gspc_last_kernel() and ",true," in b.gspc_last_kernel()
     ref = oracle_chain(ch, x0, weights, threads=16)[2]
     got = bufs[2][:ref.size].cpu().numpy().reshape(ref.shape)

@@ -156,6 +156,9 @@ def test_pack_is_a_permutation(gpu):
         # padding lanes are zero and nothing else was invented: the packed
         # bytes hold every weight at least once and otherwise only zeros
         n = b.gspc_packed_weight_bytes(Cin, Cout, K, K, g)
+        if K == 3 and (Cout // g) % 16 == 0 and (Cin // g) % 4 == 0 and Cin // g >= 8:
+            # the trailing Winograd section holds transformed filters (checked in test_gpu_winograd.py)
+            n -= g * (Cin // g // 4) * (Cout // g // 16) * 4096
         off = (-pw.storage.data_ptr()) % 256
         flat = pw.storage[off:off + n].view(torch.float32).cpu().numpy()
         vals = set(np.unique(flat).tolist())
@@ -224,7 +227,7 @@ def test_tile_table_overrides_the_planner(gpu, tmp_path):
     the listed layer (and still matches the oracle); unlisted layers are untouched."""
     import subprocess, sys, os, textwrap
     table = tmp_path / "t.tune"
-    table.write_text("# test table\n64 64 16 16 64 3 3 1 1 2 0 m 8\n")
+    table.write_text("# test table\n64 64 16 16 64 3 3 1 1 2 0 m 8\n3 64 16 16 64 3 3 1 1 2 0 x 2\n")
     code = textwrap.dedent(f"""
         import sys, numpy as np
         sys.path.insert(0, {os.path.dirname(os.path.dirname(os.path.abspath(__file__)))!r})
@@ -233,7 +236,8 @@ def test_tile_table_overrides_the_planner(gpu, tmp_path):
         from paper_2006_09791_amd import binding as b, workloads as wl
         from helpers import rel_err
         S = wl.ConvShape
-        for s in (S(64, 64, 16, 16, 64, 3, 3, 1, 1, 2), S(64, 64, 16, 16, 64, 3, 3, 1, 1, 4)):
+        b.gspc_set_winograd(0)   # the unlisted layer then shows the direct planner's own choice
+        for s in (S(64, 64, 16, 16, 64, 3, 3, 1, 1, 2), S(64, 64, 16, 16, 64, 3, 3, 1, 1, 4), S(3, 64, 16, 16, 64, 3, 3, 1, 1, 2)):
             x = wl.make_input((s.N, s.Cin, s.H, s.W), 3); w = wl.make_weight(s.Cout, s.Cin // s.groups, 3, 3, 4)
             pw = b.gspc_pack_weights(torch.from_numpy(w).cuda(), s.groups)
             y = torch.empty((s.N, s.Cout, s.H, s.W), device="cuda")
@@ -247,6 +251,8 @@ def test_tile_table_overrides_the_planner(gpu, tmp_path):
     lines = [l for l in out.strip().splitlines() if l.startswith("conv_")]
     assert lines[0].startswith("conv_mfma16<1,1,1,4,3,3,1,f32,") and lines[0].endswith("True"), out
     assert lines[1].startswith("conv_mfma16w<") and lines[1].endswith("True"), out
+    # family 'x': Winograd F(2x2, 3x3) for a layer the automatic mode would leave to the direct kernels
+    assert lines[2].startswith("conv_wino<1,1,2,2,") and lines[2].endswith("True"), out
 
 
 # Filters per group that are not a multiple of 16 (the G(g) forms of a MobileNetV2-shaped

@@ -35,7 +35,7 @@ def winograd(gpu):
     _, b = gpu
     b.gspc_set_winograd(1)
     yield b
-    b.gspc_set_winograd(0)
+    b.gspc_set_winograd(None)
 
 
 @pytest.mark.parametrize("s", SHAPES, ids=lambda s: "x".join(map(str, s)))
@@ -55,9 +55,23 @@ def test_winograd_leaves_other_layers_alone(gpu, winograd):
         assert rel_err(y, oracle.conv2d_grouped(x, w, s.stride, s.pad, s.groups, threads=8)) < TOL_F32
 
 
-def test_winograd_is_off_by_default(gpu):
-    _, _, _, name = run_conv(gpu, SHAPES[0], seed=33)
-    assert not name.startswith("conv_wino<"), name
+def test_winograd_modes(gpu):
+    """Automatic (the default): only launches that fill the chip; 0: never; 1: every eligible layer."""
+    _, b = gpu
+    small, large = SHAPES[0], SHAPES[9]
+    try:
+        assert not run_conv(gpu, small, seed=33)[3].startswith("conv_wino<")
+        y, x, w, name = run_conv(gpu, large, seed=33)
+        assert name.startswith("conv_wino<"), name
+        assert rel_err(y, oracle.conv2d_grouped(x, w, 1, 1, large.groups, threads=8)) < TOL_F32
+        b.gspc_set_winograd(0)
+        y0, _, _, name = run_conv(gpu, large, seed=33)
+        assert not name.startswith("conv_wino<"), name
+        assert rel_err(y0, y) < 1e-5   # the two methods agree far inside the tolerance
+        b.gspc_set_winograd(1)
+        assert run_conv(gpu, small, seed=33)[3].startswith("conv_wino<")
+    finally:
+        b.gspc_set_winograd(None)
 
 
 @pytest.mark.parametrize("s", [S(3, 32, 16, 16, 32, 3, 3, 1, 1, 2), S(2, 32, 9, 9, 64, 3, 3, 1, 1, 1)],
@@ -97,3 +111,27 @@ def test_winograd_wrn_chain(gpu, winograd):
     got = bufs[chain.out_buf][:n_out].cpu().numpy().reshape(chain.out_shape)
     ref = oracle_chain(chain, x0, weights)[chain.out_buf]
     assert rel_err(got, ref) < TOL_F32
+
+
+def test_packed_winograd_section(gpu):
+    """The last section of the packed buffer is U = G g G^T in matrix-core operand order:
+    [group][channel block of 4][filter tile of 16][quad][lane][4], lane l = filter l % 16 at
+    channel l // 16 of the block, value e of quad q = position (xi, nu) = (q, e)."""
+    torch, b = gpu
+    Cout, Cin, g = 64, 48, 2
+    cpg, kpg = Cin // g, Cout // g
+    w = wl.make_weight(Cout, cpg, 3, 3, 81)
+    pw = b.gspc_pack_weights(torch.from_numpy(w).cuda(), g)
+    n = b.gspc_packed_weight_bytes(Cin, Cout, 3, 3, g)
+    sec = g * (cpg // 4) * (kpg // 16) * 4096
+    off = (-pw.storage.data_ptr()) % 256
+    flat = pw.storage[off + n - sec:off + n].view(torch.float32).cpu().numpy()
+    got = flat.reshape(g, cpg // 4, kpg // 16, 4, 64, 4)
+    G = np.array([[1, 0, 0], [0.5, 0.5, 0.5], [0.5, -0.5, 0.5], [0, 0, 1]], dtype=np.float64)
+    U = np.einsum("xp,kcpq,nq->kcxn", G, w.astype(np.float64), G)   # [Cout][cpg][xi][nu]
+    lane = np.arange(64)
+    for j in range(g):
+        for cb in range(cpg // 4):
+            for mt in range(kpg // 16):
+                want = U[j * kpg + mt * 16 + lane % 16, cb * 4 + lane // 16]   # [lane][xi][nu]
+                assert np.allclose(got[j, cb, mt].transpose(1, 0, 2), want, rtol=1e-6, atol=1e-7)
