@@ -29,6 +29,7 @@ FAMILIES = {
     "m": ("conv_mfma16<", range(13)),
     "b": ("conv_mfma16b<", range(6)),
     "q": ("conv_mfma4r<", (1, 2, 4)),
+    "x": ("conv_wino<", range(7)),      # Winograd F(2x2, 3x3): fp32, 3x3, stride 1, pad 1
 }
 
 
@@ -90,8 +91,8 @@ def main():
     base = run_child(args, None)
     best = [{"family": None, "index": None, "us": r["us"], "kernel": r["kernel"]} for r in base]
     with tempfile.TemporaryDirectory() as tmp:
-        # the bf16 kernel exists for bf16 inputs only, the resident-filter kernel for fp32 only
-        for fam in (("b", "m", "q") if dtype == "bf16" else ("w", "m", "q")):
+        # the bf16 kernel exists for bf16 inputs only, the resident-filter and Winograd kernels for fp32 only
+        for fam in (("b", "m", "q") if dtype == "bf16" else ("w", "m", "q", "x")):
             prefix, indices = FAMILIES[fam]
             for idx in indices:
                 path = os.path.join(tmp, f"{fam}{idx}.tune")

@@ -161,3 +161,24 @@ def test_pointwise_form_doubles_the_3x3_layers():
         if l.KH == 3:
             assert l.Cin == l.Cout and l.groups == 4
     assert pw.out_shape == plain.out_shape
+
+
+def test_minimal_filtering_identity_used_by_the_winograd_kernel():
+    """F(2x2, 3x3): Y = A^T [(G g G^T) .* (B^T d B)] A equals the 2x2 valid correlation of a 4x4
+    patch with a 3x3 filter, and the sum over channels may be taken in the transformed domain
+    (what makes the grouped form of Section VI a set of 16 per-group GEMMs).  Checked in float64
+    on random data against the plain definition."""
+    import numpy as np
+    BT = np.array([[1, 0, -1, 0], [0, 1, 1, 0], [0, -1, 1, 0], [0, 1, 0, -1]], dtype=np.float64)
+    G = np.array([[1, 0, 0], [0.5, 0.5, 0.5], [0.5, -0.5, 0.5], [0, 0, 1]], dtype=np.float64)
+    AT = np.array([[1, 1, 1, 0], [0, 1, -1, -1]], dtype=np.float64)
+    rng = np.random.default_rng(5)
+    C = 6
+    d = rng.standard_normal((C, 4, 4))
+    g = rng.standard_normal((C, 3, 3))
+    direct = np.zeros((2, 2))
+    for i in range(2):
+        for j in range(2):
+            direct[i, j] = np.sum(d[:, i:i + 3, j:j + 3] * g)
+    M = sum((G @ g[c] @ G.T) * (BT @ d[c] @ BT.T) for c in range(C))
+    assert np.allclose(AT @ M @ AT.T, direct, rtol=1e-12, atol=1e-12)
