@@ -384,13 +384,15 @@ bool plan_wino(const ConvParams &p, const PackGeom &g, bool must_fill, WinoPlan 
     static const int order[kNumCfgX] = {1, 2, 0, 4, 5, 3, 6};
     int best = -1, best_ckb = 0;
     long best_blocks = -1;
+    bool filled = false;
     TileX bt{};
     for (int o = 0; o < kNumCfgX; ++o) {
         const int i = order[o];
         if (forced >= 0 && i != forced) continue;
-        // the small shapes (16 filters x 32 or 16 tiles, 16 x 128) repeat the V transform too often to
-        // beat the direct kernels: only on request
-        if (must_fill && forced < 0 && (i == 3 || i == 5 || i == 6)) continue;
+        // shapes with fewer filters than the group has (up to 32) repeat the V transform of a tile for
+        // every filter block and do not beat the direct kernels: only on request
+        const int filters = 16 * kCfgX[i].MI * kCfgX[i].WM;
+        if (must_fill && forced < 0 && filters < (g.KPG < 32 ? g.KPG : 32)) continue;
         TileX t;
         int k = ckb;
         if (!planx_cfg(p, g, kCfgX[i], k, &t)) {
@@ -404,12 +406,21 @@ bool plan_wino(const ConvParams &p, const PackGeom &g, bool must_fill, WinoPlan 
             best_blocks = blocks;
             bt = t;
         }
-        if (blocks >= 2 * kNumCU) break;   // the first shape that gives every compute unit two blocks
+        // the first shape that gives every compute unit two blocks - or one, for short reductions with at
+        // most two filter blocks (the offline tuner's picks among the 16x16-pixel layers at batch 64)
+        if (blocks >= 2 * kNumCU || (blocks >= kNumCU && t.oc_blocks <= 2 && t.cblks <= 16)) {
+            best = i;
+            best_ckb = k;
+            best_blocks = blocks;
+            bt = t;
+            filled = true;
+            break;
+        }
     }
     if (best < 0) return false;
     // With fewer blocks the direct kernels (which can split the reduction over waves) were faster in
     // every measured case: left to them unless Winograd is asked for explicitly.
-    if (must_fill && forced < 0 && best_blocks < 2 * kNumCU) return false;
+    if (must_fill && forced < 0 && !filled) return false;
     out->inst = best;
     out->ckb = best_ckb;
     static_assert(sizeof(TileX) <= sizeof(out->data), "plan storage too small");
