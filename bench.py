@@ -267,10 +267,14 @@ def main():
                 traffic = json.load(open(TRAFFIC_FILE)).get(name)
             except Exception:
                 traffic = None
-        if "mfma" in name and k["compute_bound"]:
+        if ("mfma" in name or "wino" in name) and k["compute_bound"]:
             ach = k["flops"] / k["time"] / 1e12
             roofline = {"bound": "mfma", "achieved": round(ach, 2), "peak": PEAK_F32_MFMA_TFLOPS,
                         "unit": "TFLOP/s", "frac": round(ach / PEAK_F32_MFMA_TFLOPS, 4)}
+            if "wino" in name:
+                # algorithmic flops are those of the direct sum (Eq. 2); the Winograd kernel needs 16/36 of
+                # the multiplications, so this fraction is an effective rate, not matrix-core occupancy
+                roofline["algorithm"] = "winograd F(2x2,3x3): executes 16/36 of the Eq. 2 multiplications"
         else:
             ach = k["bytes"] / k["time"] / 1e9
             roofline = {"bound": "hbm", "achieved": round(ach, 1), "peak": PEAK_HBM_GBS,

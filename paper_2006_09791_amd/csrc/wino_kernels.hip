@@ -382,6 +382,9 @@ bool plan_wino(const ConvParams &p, const PackGeom &g, bool must_fill, WinoPlan 
     // a tile is repeated by every filter block), then the smaller tile count (more blocks in
     // flight per compute unit, whose transform and multiply phases overlap).
     static const int order[kNumCfgX] = {1, 2, 0, 4, 5, 3, 6};
+    // (Eq. 2; below about 128 MMAC a layer sits on the launch floor of the direct kernels, which
+    // Winograd's longer prologue and epilogue cannot reach)
+    const double macs = (double)p.N * p.Cout * g.CPG * 9 * p.H * p.W;
     int best = -1, best_ckb = 0;
     long best_blocks = -1;
     bool filled = false;
@@ -420,7 +423,7 @@ bool plan_wino(const ConvParams &p, const PackGeom &g, bool must_fill, WinoPlan 
     if (best < 0) return false;
     // With fewer blocks the direct kernels (which can split the reduction over waves) were faster in
     // every measured case: left to them unless Winograd is asked for explicitly.
-    if (must_fill && forced < 0 && !filled) return false;
+    if (must_fill && forced < 0 && (!filled || macs < 128.0e6)) return false;
     out->inst = best;
     out->ckb = best_ckb;
     static_assert(sizeof(TileX) <= sizeof(out->data), "plan storage too small");
