@@ -349,6 +349,21 @@ bool plan_mfma4(const ConvParams &p, const PackGeom &g, Mfma4Plan *out) {
         if ((t.NB == 1 && blocks >= enough) || blocks >= 4L * kNumCU) break;
     }
     if (!chosen) return false;
+    // Half the pixel runs per wave when that cuts the plane into tiles with clearly fewer idle lanes
+    // (a 56x56 plane is 4 tiles of 1024 pixels at 77 % or 7 of 512 at 88 %; the offline tuner's pick, 5-10 %).
+    // Heavy filter banks only: with lighter ones the saving did not repeat at batch 256.
+    if (forced < 0 && chosen > 1 && g.Kred * MT >= 144) {
+        Tile4 t;
+        if (plan4_tile(p, g, chosen / 2, &t)) {
+            const double px = (double)p.N * p.Hout * p.Wout;
+            const double eff0 = px / ((double)best.row_blocks * best.img_blocks * 256 * chosen);
+            const double eff1 = px / ((double)t.row_blocks * t.img_blocks * 128 * chosen);
+            if (t.NB == 1 && best.NB == 1 && eff1 >= eff0 + 0.08) {
+                chosen /= 2;
+                best = t;
+            }
+        }
+    }
     out->inst = chosen;
     std::memcpy(out->data, &best, sizeof(best));
     return true;
