@@ -193,7 +193,8 @@ int gspc_set_chain_fusion(int on);
  * Y = A^T [sum_c (G g G^T) .* (B^T d B)] A: 16 instead of 36 multiplications per
  * channel and 2x2 outputs.  The result differs from the direct sum by rounding only
  * (fp32 throughout; about 1e-6 of sum |x||w| per output), but is not bit-identical
- * to it.  on < 0 (the default): used for such a layer when the launch is large enough
+ * to it; since the input transform forms differences of inputs, an infinite input
+ * can give NaN where the direct sum gives an infinity.  on < 0 (the default): used for such a layer when the launch is large enough
  * to fill the GPU, where it is the faster method; on = 0: never (every layer is the
  * direct sum); on > 0: for every such layer.  Per calling thread.  The environment
  * variable GSPC_WINOGRAD=0|1 sets the initial mode of every thread. */
