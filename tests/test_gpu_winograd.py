@@ -135,3 +135,46 @@ def test_packed_winograd_section(gpu):
             for mt in range(kpg // 16):
                 want = U[j * kpg + mt * 16 + lane % 16, cb * 4 + lane // 16]   # [lane][xi][nu]
                 assert np.allclose(got[j, cb, mt].transpose(1, 0, 2), want, rtol=1e-6, atol=1e-7)
+
+
+def _random_eligible(count, seed):
+    rng = np.random.default_rng(seed)
+    out = []
+    while len(out) < count:
+        g = int(rng.choice([1, 2, 3, 4, 8]))
+        cpg = int(rng.choice([8, 12, 16, 20, 24, 32, 64]))
+        kpg = int(rng.choice([16, 32, 48, 64, 96]))
+        h = int(rng.integers(3, 41))
+        w = h if rng.random() < 0.5 else int(rng.integers(3, 41))
+        n = int(rng.choice([1, 2, 3, 5, 9, 16, 37, 70]))
+        macs = n * g * kpg * cpg * 9 * h * w
+        if macs > 200e6 or n * g * (cpg + kpg) * h * w > 12e6:
+            continue
+        out.append(S(n, g * cpg, h, w, g * kpg, 3, 3, 1, 1, g))
+    return out
+
+
+RANDOM = _random_eligible(60, 20261127)
+_ran = {}
+
+
+@pytest.mark.parametrize("i", range(len(RANDOM)), ids=lambda i: "x".join(map(str, RANDOM[i])))
+def test_winograd_random_shapes(gpu, winograd, i):
+    """Seeded random eligible layers (odd and non-square planes, batches that do not divide the
+    images per block, 1-6 filter tiles, 2-16 channel blocks) on whatever block shape the planner picks."""
+    s = RANDOM[i]
+    y, x, w, name = run_conv(gpu, s, seed=3000 + i)
+    _ran[i] = name
+    ref = oracle.conv2d_grouped(x, w, 1, 1, s.groups, threads=8)
+    assert not np.isnan(y).any(), f"{name}: output not fully written for {s}"
+    assert rel_err(y, ref) < TOL_F32, f"{name} for {s}"
+
+
+def test_winograd_random_shapes_mostly_planned():
+    """A few of the shapes above have no Winograd plan (widths that are not a multiple of 4 with an odd
+    number of filter tiles need more staging slots than the small block shapes have) and fall back to
+    the direct kernels; most must have run the Winograd kernel for the test above to mean anything."""
+    if len(_ran) < len(RANDOM):
+        pytest.skip("runs after the parametrized test")
+    n = sum(1 for v in _ran.values() if v.startswith("conv_wino<"))
+    assert n >= 45, sorted(set(_ran.values()))
