@@ -43,6 +43,7 @@ struct Tile16 {
     int in_floats, w_floats; // per LDS buffer (a buffer is in | w | 4 spare floats)
     int ksplit;              // 1: the four waves share one pixel tile and split the reduction
     int vec_out;             // groups of four tile pixels are 16 contiguous, aligned bytes of a plane
+    int one_buf;             // single chunk with padded channels: one LDS buffer instead of two
     unsigned m_IHt, m_NB, m_ppi, m_Wout, m_rowb, m_ocb;  // multiply-high reciprocals (0 = divisor 1)
     unsigned x_bytes, w_bytes, y_bytes;                  // extents for the buffer descriptors
 };
@@ -191,10 +192,10 @@ __global__ __launch_bounds__(64 * WM * WP) void conv_mfma16(ConvParams p, Tile16
     // The staging never writes the halo columns left and right of a row: clear
     // them once, in both buffers (rows = channels x images x staged rows).
     {
-        const int rows = 2 * t.CK * t.NB * t.IHt;
+        const int per = t.CK * t.NB * t.IHt, rows = (t.one_buf ? 1 : 2) * per;
         const int right = t.XO + p.W;
         for (int i = tid; i < rows; i += NT) {
-            const int b = i >= rows / 2, rr = i - b * (rows / 2);
+            const int b = i >= per, rr = i - b * per;
             const int cimg = fast_div(rr, t.m_IHt), r = rr - cimg * t.IHt;
             const int c = fast_div(cimg, t.m_NB), img = cimg - c * t.NB;
             float *row = smem + b * buf_floats + c * t.PLANE + img * t.IMG + r * t.LW;
@@ -444,7 +445,9 @@ bool plan16_cfg(const ConvParams &p, const PackGeom &g, const Cfg16 &c, Tile16 *
         const int CK = 4 * d;
         const int wsl = (c.MI * c.WM * d * taps * 16 + NT - 1) / NT;
         const size_t in_f = (size_t)CK * t.PLANE, w_f = (size_t)wsl * NT * 4;
-        if (2 * (in_f + w_f + 4) * sizeof(float) > (size_t)(c.ksplit ? 2 * lds_budget : lds_budget)) continue;
+        // (layers with padded channels run as a single chunk and never touch the second buffer: larger
+        // tiles fit, e.g. 18 channels per group on 56-pixel rows)
+        if ((check_c ? 1 : 2) * (in_f + w_f + 4) * sizeof(float) > (size_t)(c.ksplit ? 2 * lds_budget : lds_budget)) continue;
         if ((CK * t.NB * t.IHt + rpp - 1) / rpp > (p.KH == 7 ? kTmax16Stem : kTmax16)) continue;
         if (wsl > kWmax16) continue;
         best = d;
@@ -452,6 +455,7 @@ bool plan16_cfg(const ConvParams &p, const PackGeom &g, const Cfg16 &c, Tile16 *
     if (!best) return false;
     t.CK = 4 * best;
     t.nchunks = cblks / best;
+    t.one_buf = check_c ? 1 : 0;
     t.m_IHt = div_magic(t.IHt);
     t.m_NB = div_magic(t.NB);
     t.m_ppi = div_magic(t.TH * p.Wout);
@@ -596,7 +600,7 @@ bool plan16(const ConvParams &p, const PackGeom &g, int *cfg_idx, Tile16 *t_out)
 
 template <int MI, int NI, int WM, int WP, int KH, int KW, int S, typename TIN, bool VO>
 hipError_t launch16_vo(const ConvParams &p, const Tile16 &t, hipStream_t s) {
-    size_t lds = 2 * ((size_t)t.in_floats + t.w_floats + 4) * sizeof(float);
+    size_t lds = (t.one_buf ? 1 : 2) * ((size_t)t.in_floats + t.w_floats + 4) * sizeof(float);
     if (t.ksplit && lds < (size_t)WM * WP * MI * NI * 1024) lds = (size_t)WM * WP * MI * NI * 1024;
     dim3 grid(t.row_blocks * t.img_blocks, p.groups * t.oc_blocks);
     auto kern = conv_mfma16<MI, NI, WM, WP, KH, KW, S, TIN, VO>;
