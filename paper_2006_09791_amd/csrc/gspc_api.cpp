@@ -164,6 +164,11 @@ int prepare_conv(const void *input, const gspc_packed_t *pw, int N, int Cin, int
             p->W = p->Wout = best_w;
             p->H = p->Hout = hw / best_w;
         }
+    } else if (KH == 1 && KW == 1 && stride == 1 && pad == 0 && H > 1 && (H * W) % 4 != 0 && H * W <= 256) {
+        // Planes whose size is not a multiple of 4 (7x7, 5x5 ...): one row of H*W elements.  The plain
+        // 16x16x4 kernel then stages blocks of four channels as single aligned rows.
+        p->W = p->Wout = H * W;
+        p->H = p->Hout = 1;
     }
     return GSPC_OK;
 }

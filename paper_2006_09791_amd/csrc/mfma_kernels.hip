@@ -44,6 +44,7 @@ struct Tile16 {
     int ksplit;              // 1: the four waves share one pixel tile and split the reduction
     int vec_out;             // groups of four tile pixels are 16 contiguous, aligned bytes of a plane
     int one_buf;             // single chunk with padded channels: one LDS buffer instead of two
+    int flat4;               // 1x1 on a plane of HW % 4 != 0 elements, one image per block: four channels staged as one row
     unsigned m_IHt, m_NB, m_ppi, m_Wout, m_rowb, m_ocb;  // multiply-high reciprocals (0 = divisor 1)
     unsigned x_bytes, w_bytes, y_bytes;                  // extents for the buffer descriptors
 };
@@ -117,7 +118,15 @@ __global__ __launch_bounds__(64 * WM * WP) void conv_mfma16(ConvParams p, Tile16
         const int task = row0 + k * rpp;
         xoff[k] = kOob;
         xlds[k] = spare;
-        if (k < t.xslots && task < t.tasks && colv * vw < p.W) {
+        if (t.flat4) {
+            // The four planes of a 4-channel block are 4*HW contiguous floats (16-byte aligned, since the
+            // channel count per group is a multiple of 4) both in global memory and in the tile (PLANE = HW):
+            // one staged row per block of channels, 16 bytes per thread, whatever HW is.
+            if (k < t.xslots && task < t.tasks && colv < p.W) {
+                xlds[k] = (task * 4 * t.PLANE + colv * 4) * 4;
+                if (n0 < p.N) xoff[k] = ((((unsigned)n0 * p.Cin + j * p.CPG + 4 * task) * HW) + colv * 4) * ES;
+            }
+        } else if (k < t.xslots && task < t.tasks && colv * vw < p.W) {
             const int cimg = fast_div(task, t.m_IHt), r = task - cimg * t.IHt;
             const int c = fast_div(cimg, t.m_NB), img = cimg - c * t.NB;
             const int ih = ih0 + r, n = n0 + img;
@@ -408,6 +417,11 @@ bool plan16_cfg(const ConvParams &p, const PackGeom &g, const Cfg16 &c, Tile16 *
     t.ksplit = c.ksplit;
     if (!split_pixels(p, PB, &t.NB, &t.TH)) return false;
     t.IHt = (t.TH - 1) * p.stride + p.KH;
+    // 1x1 layers on planes handed over as one row of HW % 4 != 0 elements (7x7, 5x5 ...): one image per
+    // block, channel pitch HW exactly, so that four channels can be staged as one aligned row
+    t.flat4 = p.KH == 1 && p.KW == 1 && p.stride == 1 && p.pad == 0 && p.H == 1 && p.W % 4 != 0 && !p.in_bf16 &&
+              g.CPGp == g.CPG && p.W <= NT && PB < 2 * p.W;
+    if (t.flat4) t.NB = 1;
     t.vec = p.W % 4 == 0;
     if (t.vec) {
         t.XO = 4 * ((p.pad + 3) / 4);
@@ -426,8 +440,9 @@ bool plan16_cfg(const ConvParams &p, const PackGeom &g, const Cfg16 &c, Tile16 *
             best_pad = pad;
         }
     }
-    t.PLANE = plane0 + best_pad;
-    const int cols = t.vec ? p.W / 4 : p.W;
+    t.PLANE = t.flat4 ? p.W : plane0 + best_pad;
+    if (t.flat4) t.vec = 1;   // 16-byte loads and LDS writes
+    const int cols = t.vec && !t.flat4 ? p.W / 4 : p.W;
     t.tpr_log2 = 0;
     while ((1 << t.tpr_log2) < cols) ++t.tpr_log2;
     if ((1 << t.tpr_log2) > NT) return false;
@@ -448,7 +463,7 @@ bool plan16_cfg(const ConvParams &p, const PackGeom &g, const Cfg16 &c, Tile16 *
         // (layers with padded channels run as a single chunk and never touch the second buffer: larger
         // tiles fit, e.g. 18 channels per group on 56-pixel rows)
         if ((check_c ? 1 : 2) * (in_f + w_f + 4) * sizeof(float) > (size_t)(c.ksplit ? 2 * lds_budget : lds_budget)) continue;
-        if ((CK * t.NB * t.IHt + rpp - 1) / rpp > (p.KH == 7 ? kTmax16Stem : kTmax16)) continue;
+        if (((t.flat4 ? d : CK * t.NB * t.IHt) + rpp - 1) / rpp > (p.KH == 7 ? kTmax16Stem : kTmax16)) continue;
         if (wsl > kWmax16) continue;
         best = d;
     }
@@ -463,7 +478,7 @@ bool plan16_cfg(const ConvParams &p, const PackGeom &g, const Cfg16 &c, Tile16 *
     t.m_rowb = div_magic(t.row_blocks);
     t.m_ocb = div_magic(t.oc_blocks);
     t.vec_out = (t.TH * p.Wout) % 4 == 0 && (p.Hout * p.Wout) % 4 == 0;
-    t.tasks = t.CK * t.NB * t.IHt;
+    t.tasks = t.flat4 ? t.CK / 4 : t.CK * t.NB * t.IHt;
     t.xslots = (t.tasks + rpp - 1) / rpp;
     t.wslots = (c.MI * c.WM * best * taps * 16 + NT - 1) / NT;
     t.in_floats = t.CK * t.PLANE;
@@ -511,7 +526,7 @@ bool plan16(const ConvParams &p, const PackGeom &g, int *cfg_idx, Tile16 *t_out)
     if (pointwise && p.Hout * p.Wout <= 64) {
         Tile16 t;
         if (plan16_cfg(p, g, kCfg16[5], &t) &&
-            (long)t.row_blocks * t.img_blocks * t.oc_blocks * p.groups >= 4 * kNumCU) {
+            (long)t.row_blocks * t.img_blocks * t.oc_blocks * p.groups >= 2 * kNumCU) {
             *cfg_idx = 5;
             *t_out = t;
             return true;
