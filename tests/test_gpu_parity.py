@@ -280,3 +280,33 @@ PADDED_TILES = [
 def test_filters_per_group_not_a_multiple_of_16(gpu, s):
     name = check(gpu, s, seed=23)
     assert name.startswith("conv_mfma16<"), name
+
+
+# 1x1 layers on planes whose size is not a multiple of 4: the plane travels as one row of H*W elements
+# and, where a block covers one image, four channels at a time are staged as one aligned row.
+ODD_PLANES = [
+    S(3, 64, 5, 5, 64, 1, 1, 1, 0, 1),
+    S(2, 32, 9, 9, 48, 1, 1, 1, 0, 2),       # grouped, three filter tiles
+    S(5, 128, 13, 13, 64, 1, 1, 1, 0, 1),    # 169-element planes
+    S(2, 64, 15, 15, 32, 1, 1, 1, 0, 1),     # 225
+    S(3, 24, 3, 3, 16, 1, 1, 1, 0, 1),       # 9: smaller than any tile
+    S(70, 160, 7, 7, 960, 1, 1, 1, 0, 1),    # MobileNetV2 expansion at a batch that fills the chip
+    S(1, 960, 7, 7, 160, 1, 1, 1, 0, 1),     # projection at batch 1: 240 k-steps
+    S(2, 6, 7, 7, 16, 1, 1, 1, 0, 1),        # padded channels: single row, but no four-channel staging
+    S(4, 40, 7, 9, 40, 1, 1, 1, 0, 2),       # non-square, 63 elements, 20 filters per group
+]
+
+
+@pytest.mark.parametrize("s", ODD_PLANES, ids=lambda s: "x".join(map(str, s)))
+def test_pointwise_on_odd_planes(gpu, s):
+    check(gpu, s, seed=29)
+
+
+def test_pointwise_on_odd_planes_bf16(gpu):
+    torch, b = gpu
+    s = S(3, 64, 7, 7, 64, 1, 1, 1, 0, 1)
+    y, x, w, name = run_conv(gpu, s, seed=30, dtype=b.GSPC_BF16)
+    _, xr = wl.round_to_bf16(x)
+    _, wr = wl.round_to_bf16(w)
+    ref = oracle.conv2d_grouped(xr, wr, 1, 0, 1, threads=8)
+    assert rel_err(y, ref) < 1e-4, name
