@@ -52,7 +52,7 @@ def main():
     ap.add_argument("--traffic-probe", action="store_true",
                     help="first run a plain 256 MiB device copy three times: the known-size kernel "
                          "against which rocprofv3's FETCH_SIZE / WRITE_SIZE counters are scaled")
-    ap.add_argument("--sweep", choices=["wrn", "wrn_n256", "resnet_bf16", "depthwise", "blocks", "latency", "winograd"],
+    ap.add_argument("--sweep", choices=["wrn", "wrn_n256", "resnet_bf16", "depthwise", "blocks", "latency", "winograd", "mobilenetv2"],
                     help="instead of the headline step, time every layer of a configuration family "
                          "and print one JSON line with a row per layer")
     ap.add_argument("--fusion", action="store_true",
@@ -141,6 +141,31 @@ def main():
                     rows.append({"layer": d["layer"], "direct_kernel": d["kernel"], "direct_us": d["us"],
                                  "direct_frac_mfma": d["frac_mfma"], "winograd_kernel": w["kernel"], "winograd_us": w["us"],
                                  "speedup": round(d["us"] / w["us"], 3), "default_kernel": a["kernel"], "default_us": a["us"]})
+        elif args.sweep == "mobilenetv2":
+            # the MobileNetV2-shaped network (Section IV-A) at batch 64, G(g) for g in {2,4,8,16} and the
+            # depthwise original G(N): whole forward passes as recorded chains
+            rows = []
+            for g in (2, 4, 8, 16, None):
+                ch = wl.mobilenetv2_chain(64, g)
+                weights = ch.make_weights(6)
+                packed = [b.gspc_pack_weights(torch.from_numpy(w).to(dev), gg)
+                          for w, gg in zip(weights, ch.weight_groups)]
+                bufs = [torch.empty(max(n, 1), dtype=torch.float32, device=dev) for n in ch.buf_elems]
+                bufs[0].copy_(torch.from_numpy(wl.make_input(ch.input_shape, 1)).reshape(-1))
+                lc = b.LayerChain(ch.layers, packed, bufs)
+                for _ in range(3):
+                    b.gspc_run_layer_chain(lc)
+                torch.cuda.synchronize()
+                reps = 20
+                ta = time.perf_counter()
+                for _ in range(reps):
+                    b.gspc_run_layer_chain(lc)
+                torch.cuda.synchronize()
+                ms = (time.perf_counter() - ta) / reps * 1e3
+                rows.append({"network": f"mobilenetv2-shaped {'G(N) depthwise' if g is None else 'g=' + str(g)} N=64",
+                             "layers": len(ch.layers), "gmacs_per_pass": round(ch.macs() / 1e9, 2),
+                             "ms": round(ms, 3), "tmacs": round(ch.macs() / ms / 1e9, 1)})
+                del lc, bufs, packed
         elif args.sweep == "blocks":
             # depthwise 3x3 + pointwise 1x1 blocks, as two kernels and with chain fusion
             rows = layer_timing.time_blocks(wl.depthwise_pairs(256), inner=8, reps=5)
