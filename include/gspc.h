@@ -187,8 +187,8 @@ int gspc_set_graph_mode(int on);
 int gspc_set_chain_fusion(int on);
 
 /* Winograd F(2x2, 3x3) evaluation (the grouped Winograd convolution that Section VI
- * of the paper leaves as future work).  fp32 3x3, stride-1, pad-1 layers with a
- * multiple of 16 filters and a multiple of 4 (at least 8) channels per group can be
+ * of the paper leaves as future work).  fp32 3x3, stride-1, pad-1 layers with at
+ * least 12 filters and a multiple of 4 (at least 8) channels per group can be
  * evaluated through the minimal-filtering identity
  * Y = A^T [sum_c (G g G^T) .* (B^T d B)] A: 16 instead of 36 multiplications per
  * channel and 2x2 outputs.  The result differs from the direct sum by rounding only

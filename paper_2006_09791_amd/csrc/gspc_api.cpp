@@ -229,9 +229,9 @@ PackGeom make_pack_geom(int Cin, int Cout, int KH, int KW, int groups, int dtype
         g.bf16_bytes = (size_t)groups * g.nchunks_b * g.ks_b * g.mtiles_b * 1024;
     }
     g.total_bytes = g.bf16_bytes ? g.bf16_offset + g.bf16_bytes : g.mfma_offset + g.mfma_bytes;
-    if (dtype == GSPC_F32 && KH == 3 && KW == 3 && g.KPG % 16 == 0 && g.CPG % 4 == 0 && g.CPG >= 8) {
+    if (dtype == GSPC_F32 && KH == 3 && KW == 3 && g.KPG >= 12 && g.CPG % 4 == 0 && g.CPG >= 8) {
         g.wino_offset = (g.total_bytes + 255) / 256 * 256;
-        g.wino_bytes = (size_t)groups * (g.CPG / 4) * (g.KPG / 16) * 4096;
+        g.wino_bytes = (size_t)groups * (g.CPG / 4) * ((g.KPG + 15) / 16) * 4096;
         g.total_bytes = g.wino_offset + g.wino_bytes;
     }
     return g;

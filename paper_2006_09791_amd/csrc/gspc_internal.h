@@ -47,8 +47,9 @@ struct PackGeom {
     // unit 4*s + l/16 of filter l%16 (zeros past the last unit).
     int ckb, ks_b, nchunks_b, mtiles_b;
     size_t bf16_bytes, bf16_offset;
-    // Winograd F(2x2, 3x3) section (GSPC_F32 handles, 3x3, KPG % 16 == 0, CPG % 4 == 0,
-    // CPG >= 8): fp32 U = G g G^T as [g][CPG/4][KPG/16][4][64 lanes][4]; lane l holds
+    // Winograd F(2x2, 3x3) section (GSPC_F32 handles, 3x3, KPG >= 12, CPG % 4 == 0,
+    // CPG >= 8): fp32 U = G g G^T as [g][CPG/4][ceil(KPG/16)][4][64 lanes][4] (filters
+    // past KPG in the last tile are zero); lane l holds
     // filter l % 16 of its tile at channel 4*cblk + l / 16, and its four values in
     // quad q are the transformed-domain positions 4*q .. 4*q + 3 (position = 4*xi + nu).
     size_t wino_bytes, wino_offset;

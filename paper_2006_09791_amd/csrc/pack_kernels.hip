@@ -73,12 +73,16 @@ __global__ void pack_wino_kernel(const float *__restrict__ w, float *__restrict_
     r /= 64;
     const int quad = (int)(r % 4);
     r /= 4;
-    const int mtiles = a.KPG / 16, cblks = a.CPG / 4;
+    const int mtiles = (a.KPG + 15) / 16, cblks = a.CPG / 4;
     const int mt = (int)(r % mtiles);
     r /= mtiles;
     const int cb = (int)(r % cblks);
     const int j = (int)(r / cblks);
     const int xi = quad, nu = e;   // position 4*quad + e = 4*xi + nu
+    if (mt * 16 + lane % 16 >= a.KPG) {   // padding filter of the last tile
+        out[d] = 0.f;
+        return;
+    }
     const int oc = j * a.KPG + mt * 16 + lane % 16, c = cb * 4 + lane / 16;
     const float *g = w + (size_t)oc * a.Kred + (size_t)c * 9;
     const float G[4][3] = {{1.f, 0.f, 0.f}, {0.5f, 0.5f, 0.5f}, {0.5f, -0.5f, 0.5f}, {0.f, 0.f, 1.f}};

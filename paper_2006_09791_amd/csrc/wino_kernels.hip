@@ -18,7 +18,7 @@
 //   registers, so the inverse transform A^T M A needs no exchange between lanes; the
 //   2x2 results go straight to NCHW (output reshape fused away).
 //
-// Stride 1, pad 1, fp32, KPG a multiple of 16, CPG a multiple of 4.
+// Stride 1, pad 1, fp32, KPG >= 12 (the last filter tile zero-padded), CPG a multiple of 4.
 #include <cstdlib>
 #include <cstring>
 
@@ -232,10 +232,13 @@ __global__ __launch_bounds__(64 * WM * WP, 2) void conv_wino(ConvParams p, TileX
                 float y00 = s0[0] + s0[1] + s0[2], y01 = s0[1] - s0[2] - s0[3];
                 float y10 = s1[0] + s1[1] + s1[2], y11 = s1[1] - s1[2] - s1[3];
                 const unsigned so = (oc0 + mi * 16 + r) * HW * 4;
+                // filters past KPG in a zero-padded last tile neither load a residual nor store
+                const bool fk = oc0 + mi * 16 + 4 * (lane >> 4) + r < (unsigned)p.KPG;
+                const unsigned p0 = fk ? o0 : kOob, p1 = fk ? o1 : kOob;
                 if (!t.wodd) {
                     if (p.res) {
-                        const u32x2 ra = __builtin_amdgcn_raw_buffer_load_b64(rr, o0, so, 0);
-                        const u32x2 rb2 = __builtin_amdgcn_raw_buffer_load_b64(rr, o1, so, 0);
+                        const u32x2 ra = __builtin_amdgcn_raw_buffer_load_b64(rr, p0, so, 0);
+                        const u32x2 rb2 = __builtin_amdgcn_raw_buffer_load_b64(rr, p1, so, 0);
                         y00 += __uint_as_float(ra.x);
                         y01 += __uint_as_float(ra.y);
                         y10 += __uint_as_float(rb2.x);
@@ -247,14 +250,14 @@ __global__ __launch_bounds__(64 * WM * WP, 2) void conv_wino(ConvParams p, TileX
                         y10 = fmaxf(y10, 0.f);
                         y11 = fmaxf(y11, 0.f);
                     }
-                    __builtin_amdgcn_raw_buffer_store_b64(u32x2{__float_as_uint(y00), __float_as_uint(y01)}, ry, o0, so, 0);
-                    __builtin_amdgcn_raw_buffer_store_b64(u32x2{__float_as_uint(y10), __float_as_uint(y11)}, ry, o1, so, 0);
+                    __builtin_amdgcn_raw_buffer_store_b64(u32x2{__float_as_uint(y00), __float_as_uint(y01)}, ry, p0, so, 0);
+                    __builtin_amdgcn_raw_buffer_store_b64(u32x2{__float_as_uint(y10), __float_as_uint(y11)}, ry, p1, so, 0);
                 } else {
-                    const unsigned o0b = c1 ? o0 + 4 : kOob, o1b = c1 ? o1 + 4 : kOob;
+                    const unsigned o0b = c1 ? p0 + 4 : kOob, o1b = c1 ? p1 + 4 : kOob;
                     if (p.res) {
-                        y00 += __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rr, o0, so, 0));
+                        y00 += __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rr, p0, so, 0));
                         y01 += __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rr, o0b, so, 0));
-                        y10 += __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rr, o1, so, 0));
+                        y10 += __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rr, p1, so, 0));
                         y11 += __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rr, o1b, so, 0));
                     }
                     if (p.relu) {
@@ -263,9 +266,9 @@ __global__ __launch_bounds__(64 * WM * WP, 2) void conv_wino(ConvParams p, TileX
                         y10 = fmaxf(y10, 0.f);
                         y11 = fmaxf(y11, 0.f);
                     }
-                    __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(y00), ry, o0, so, 0);
+                    __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(y00), ry, p0, so, 0);
                     __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(y01), ry, o0b, so, 0);
-                    __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(y10), ry, o1, so, 0);
+                    __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(y10), ry, p1, so, 0);
                     __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(y11), ry, o1b, so, 0);
                 }
             }
@@ -289,7 +292,7 @@ bool planx_cfg(const ConvParams &p, const PackGeom &g, const CfgX &c, int ckb, T
     const int PT = 16 * c.NI * c.WP, NT = 64 * c.WM * c.WP, MIWM = c.MI * c.WM, CK = 4 * ckb, VP = PT + 16;
     TileX t{};
     t.cblks = g.CPG / 4;
-    t.mtiles = g.KPG / 16;
+    t.mtiles = (g.KPG + 15) / 16;
     if (t.mtiles % MIWM || t.cblks % ckb) return false;
     t.TC = (p.W + 1) / 2;
     t.TRtot = (p.H + 1) / 2;

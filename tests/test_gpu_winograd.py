@@ -26,6 +26,10 @@ SHAPES = [
     S(2, 24, 9, 13, 32, 3, 3, 1, 1, 2),      # 12 channels per group (one 4-channel block per chunk), odd plane
     S(1, 256, 14, 14, 256, 3, 3, 1, 1, 1),   # long reduction: 32 chunks of 8 channels
     S(70, 32, 32, 32, 32, 3, 3, 1, 1, 2),    # enough blocks for the largest block shape
+    S(2, 192, 14, 14, 192, 3, 3, 1, 1, 8),   # 24 filters per group: two tiles, the second half padding
+    S(3, 240, 7, 7, 240, 3, 3, 1, 1, 4),     # 60 filters per group
+    S(2, 48, 12, 12, 48, 3, 3, 1, 1, 4),     # 12 filters per group: one tile, a quarter padding
+    S(2, 32, 9, 12, 40, 3, 3, 1, 1, 1),      # 40 filters, odd height
     S(1, 16, 6, 132, 32, 3, 3, 1, 1, 2),     # 66 tile columns: wider than the 64-tile shapes (the 128-tile shape or none)
 ]
 
@@ -49,7 +53,7 @@ def test_winograd_matches_the_definition(gpu, winograd, s):
 
 def test_winograd_leaves_other_layers_alone(gpu, winograd):
     for s in (S(2, 32, 16, 16, 32, 3, 3, 2, 1, 1), S(2, 32, 16, 16, 32, 1, 1, 1, 0, 1),
-              S(2, 32, 16, 16, 32, 3, 3, 1, 0, 1), S(2, 32, 16, 16, 24, 3, 3, 1, 1, 1)):
+              S(2, 32, 16, 16, 32, 3, 3, 1, 0, 1), S(2, 32, 16, 16, 8, 3, 3, 1, 1, 1)):
         y, x, w, name = run_conv(gpu, s, seed=32)
         assert not name.startswith("conv_wino<"), name
         assert rel_err(y, oracle.conv2d_grouped(x, w, s.stride, s.pad, s.groups, threads=8)) < TOL_F32
@@ -74,7 +78,8 @@ def test_winograd_modes(gpu):
         b.gspc_set_winograd(None)
 
 
-@pytest.mark.parametrize("s", [S(3, 32, 16, 16, 32, 3, 3, 1, 1, 2), S(2, 32, 9, 9, 64, 3, 3, 1, 1, 1)],
+@pytest.mark.parametrize("s", [S(3, 32, 16, 16, 32, 3, 3, 1, 1, 2), S(2, 32, 9, 9, 64, 3, 3, 1, 1, 1),
+                               S(2, 96, 12, 12, 96, 3, 3, 1, 1, 4)],   # 24 filters per group: padded tile
                          ids=lambda s: "x".join(map(str, s)))
 def test_winograd_with_residual_and_relu(gpu, winograd, s):
     torch, b = gpu
@@ -143,7 +148,7 @@ def _random_eligible(count, seed):
     while len(out) < count:
         g = int(rng.choice([1, 2, 3, 4, 8]))
         cpg = int(rng.choice([8, 12, 16, 20, 24, 32, 64]))
-        kpg = int(rng.choice([16, 32, 48, 64, 96]))
+        kpg = int(rng.choice([12, 16, 24, 32, 40, 48, 60, 64, 96]))
         h = int(rng.integers(3, 41))
         w = h if rng.random() < 0.5 else int(rng.integers(3, 41))
         n = int(rng.choice([1, 2, 3, 5, 9, 16, 37, 70]))
