@@ -293,7 +293,11 @@ bool planx_cfg(const ConvParams &p, const PackGeom &g, const CfgX &c, int ckb, T
     TileX t{};
     t.cblks = g.CPG / 4;
     t.mtiles = (g.KPG + 15) / 16;
-    if (t.mtiles % MIWM || t.cblks % ckb) return false;
+    // Whole filter tiles per block; an odd tile count may leave up to a quarter of the last block's
+    // tiles empty (its U loads then read rows of other tiles or, past the section, zeros: products
+    // that the store mask drops).
+    const int spill = (MIWM - t.mtiles % MIWM) % MIWM;
+    if (spill * 4 > t.mtiles || t.cblks % ckb) return false;
     t.TC = (p.W + 1) / 2;
     t.TRtot = (p.H + 1) / 2;
     if (t.TC > PT) return false;
@@ -327,7 +331,7 @@ bool planx_cfg(const ConvParams &p, const PackGeom &g, const CfgX &c, int ckb, T
     if (t.xslots > kTmaxX) return false;
     t.row_blocks = (t.TRtot + t.TR - 1) / t.TR;
     t.img_blocks = (p.N + t.NB - 1) / t.NB;
-    t.oc_blocks = t.mtiles / MIWM;
+    t.oc_blocks = (t.mtiles + MIWM - 1) / MIWM;
     t.wodd = p.W % 2;
     t.m_IHt = div_magic(t.IHt);
     t.m_NB = div_magic(t.NB);

@@ -30,6 +30,8 @@ SHAPES = [
     S(3, 240, 7, 7, 240, 3, 3, 1, 1, 4),     # 60 filters per group
     S(2, 48, 12, 12, 48, 3, 3, 1, 1, 4),     # 12 filters per group: one tile, a quarter padding
     S(2, 32, 9, 12, 40, 3, 3, 1, 1, 1),      # 40 filters, odd height
+    S(2, 144, 28, 28, 144, 3, 3, 1, 1, 2),   # 72 filters per group: five tiles in three blocks of two
+    S(3, 144, 12, 12, 144, 3, 3, 1, 1, 1),   # 144 filters: nine tiles
     S(1, 16, 6, 132, 32, 3, 3, 1, 1, 2),     # 66 tile columns: wider than the 64-tile shapes (the 128-tile shape or none)
 ]
 
