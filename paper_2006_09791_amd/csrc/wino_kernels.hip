@@ -293,11 +293,11 @@ bool planx_cfg(const ConvParams &p, const PackGeom &g, const CfgX &c, int ckb, T
     TileX t{};
     t.cblks = g.CPG / 4;
     t.mtiles = (g.KPG + 15) / 16;
-    // Whole filter tiles per block; an odd tile count may leave up to a quarter of the last block's
+    // Whole filter tiles per block; an odd tile count may leave up to a third of the tile count empty in the last block's
     // tiles empty (its U loads then read rows of other tiles or, past the section, zeros: products
     // that the store mask drops).
     const int spill = (MIWM - t.mtiles % MIWM) % MIWM;
-    if (spill * 4 > t.mtiles || t.cblks % ckb) return false;
+    if (spill * 3 > t.mtiles || t.cblks % ckb) return false;
     t.TC = (p.W + 1) / 2;
     t.TRtot = (p.H + 1) / 2;
     if (t.TC > PT) return false;
