@@ -174,8 +174,8 @@ typedef struct gspc_layer {
  * the feature off and releases them, gspc_set_graph_mode(1) turns it back on. */
 int gspc_set_graph_mode(int on);
 
-/* Depth fusion of layer chains (Section 2.1 / Eq. 1: a grouped convolution only
- * mixes the channels of one group).  By default gspc_run_layer_chain evaluates a
+/* Depth fusion of layer chains (Section II, Fig. 2: a grouped convolution only
+ * mixes the channels of one group; Section III-A: groups are independent).  By default gspc_run_layer_chain evaluates a
  * run of consecutive fp32 CONV steps that share N, C, H, W and groups >= 2,
  * with 3x3 kernels, stride 1, pad 1, Cin = Cout and at most 32 channels per
  * group, in one kernel per run: one workgroup per (image, group) keeps the

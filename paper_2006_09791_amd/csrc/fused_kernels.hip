@@ -1,8 +1,8 @@
 // Depth fusion of consecutive grouped 3x3 convolutions of a layer chain.
 //
-// A grouped convolution only mixes the channels of one group (Eq. 1 of arXiv
-// 2006.09791 restricted to a group, the independence Algorithm 1 parallelises
-// over).  When consecutive layers have the same shape and the same g, stride 1
+// A grouped convolution only mixes the channels of one group (Section II and
+// Fig. 2 of arXiv 2006.09791; Section III-A: there is no data dependency
+// between groups, which is what Algorithm 1 parallelises over).  When consecutive layers have the same shape and the same g, stride 1
 // and Cin = Cout, group j of every one of them depends on group j of the
 // chain's input alone: the whole run can be evaluated per (image, group) with
 // the activations never leaving the CU.  One block owns one (image, group): its

@@ -58,7 +58,7 @@ def test_wrn_chain_n3_g4():
     assert rel_err(got, ref) < TOL_F32
 
 
-@pytest.mark.parametrize("g", [2, 32])
+@pytest.mark.parametrize("g", [2, 4, 8, 16, 32])
 def test_resnet34_chain_n1(g):
     chain = wl.resnet34_chain(1, g)
     got, ref = _run(chain, 3, wl.make_seed(3, 999, g))

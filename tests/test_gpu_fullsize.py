@@ -120,6 +120,40 @@ def test_resnet34_layers_batch256_bf16(g):
                        tol_unrounded=TOL_BF16)
 
 
+@pytest.mark.parametrize("idx,g", [(0, 2), (0, 8), (0, 32), (1, 32), (2, 8), (2, 32), (4, 32), (6, 32)])
+def test_resnet34_layers_batch256_bf16_whole_images(idx, g):
+    """Every output channel of a block of images at the batch-256 size (the other
+    test samples a few filters): the wide-store epilogues are compared element by
+    element over whole images, first and last of the batch included, and a second run
+    must give the same bits over the whole tensor."""
+    import torch
+    from paper_2006_09791_amd import binding as b
+    s = wl.resnet34_grouped_shapes(256, g)[idx]
+    seed = wl.make_seed(5, 50 + idx, g)
+    dev = torch.device("cuda:0")
+    b.gspc_set_stream()
+    b.gspc_force_path(b.PATH_AUTO)
+    x = wl.make_input((s.N, s.Cin, s.H, s.W), seed)
+    w = wl.make_weight(s.Cout, s.Cin // s.groups, s.KH, s.KW, seed)
+    pw = b.gspc_pack_weights(torch.from_numpy(w).to(dev), s.groups, b.GSPC_BF16)
+    xd = b.gspc_pack_input_bf16(torch.from_numpy(x).to(dev))
+    ys = []
+    for rep in range(2):
+        y = torch.full((s.N, s.Cout) + tuple(b.gspc_output_dims(s.H, s.W, 3, 3, s.stride, 1)), float("nan"),
+                       dtype=torch.float32, device=dev)
+        b.gspc_conv2d_grouped(xd, pw, s.N, s.Cin, s.H, s.W, s.Cout, 3, 3, s.stride, 1, s.groups, y)
+        torch.cuda.synchronize()
+        ys.append(y)
+    name = b.gspc_last_kernel()
+    assert torch.equal(ys[0], ys[1]), name             # no NaN left, same bits
+    imgs = [0, 1, 2, 3, 100, 101, 254, 255]
+    got = ys[0][imgs].cpu().numpy()
+    _, xr = wl.round_to_bf16(x[imgs])
+    _, wr = wl.round_to_bf16(w)
+    ref = oracle.conv2d_grouped(xr, wr, s.stride, s.pad, s.groups, threads=16)
+    assert rel_err(got, ref) < 1e-4, (name, s)
+
+
 def test_depthwise_batched_fp32():
     # batched re-run of the MobileNet-shaped depthwise layers (HBM-bound kernel at a size that fills the GPU)
     for i, (dw, _) in enumerate(wl.depthwise_pairs(32)):

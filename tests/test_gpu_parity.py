@@ -129,7 +129,7 @@ def test_wrn_layers_n4(gpu, g):
         check(gpu, s, seed=wl.make_seed(2, i, g))
 
 
-@pytest.mark.parametrize("g", [2, 8, 32])
+@pytest.mark.parametrize("g", [2, 4, 8, 16, 32])
 def test_resnet_layers_n1(gpu, g):
     for i, s in enumerate(wl.resnet34_grouped_shapes(1, g)):
         check(gpu, s, seed=wl.make_seed(3, i, g))

@@ -1,6 +1,6 @@
 """GPU parity of the Winograd F(2x2, 3x3) path (the grouped Winograd convolution that
 Section VI of the paper names as future work) against the oracle's plain definition of
-the grouped convolution (Eq. 1).  The identity is exact in real arithmetic; in fp32 the
+the grouped convolution (Section II, Fig. 2).  The identity is exact in real arithmetic; in fp32 the
 transforms add a few roundings of magnitude sum |x||w| * 2^-24, far inside the 1e-4 bar
 of the direct path, which is therefore kept."""
 import numpy as np

@@ -330,15 +330,120 @@ def test_p11_table2_mac_differences():
 
 
 # --------------------------------------------------------------------------
-# Chain helpers.
+# Chain helpers, pinned with numpy alone (no optional import decides whether
+# these run).
 # --------------------------------------------------------------------------
-def test_chain_helpers():
-    torch = pytest.importorskip("torch")
+def test_relu_and_add():
     x = _rand((2, 3, 9, 8), 21)
     assert np.array_equal(oracle.relu(x), np.maximum(x, 0))
     assert np.array_equal(oracle.add(x, 2 * x), x + 2 * x)
-    ref = torch.nn.functional.max_pool2d(torch.from_numpy(x), 3, 2, 1).numpy()
-    assert np.array_equal(oracle.maxpool2d(x, 3, 2, 1), ref)
+
+
+@pytest.mark.parametrize("H,W,k,stride,pad", [(9, 8, 3, 2, 1), (7, 7, 3, 2, 1), (6, 5, 2, 2, 0),
+                                              (5, 6, 3, 1, 1), (112, 112, 3, 2, 1)])
+def test_maxpool_against_windows_of_a_padded_copy(H, W, k, stride, pad):
+    # Independent construction: pad a copy with -inf, take every k x k window
+    # with numpy's sliding-window view, subsample by the stride.  Catches a
+    # wrong window origin, a zero (instead of ignored) border, a stride slip.
+    N, C = (1, 2) if H > 50 else (2, 3)
+    x = _rand((N, C, H, W), 24)
+    xp = np.pad(x, ((0, 0), (0, 0), (pad, pad), (pad, pad)), constant_values=-np.inf)
+    win = np.lib.stride_tricks.sliding_window_view(xp, (k, k), axis=(2, 3))
+    ref = win[:, :, ::stride, ::stride].max(axis=(4, 5))
+    got = oracle.maxpool2d(x, k, stride, pad)
+    assert got.shape == (N, C, (H + 2 * pad - k) // stride + 1, (W + 2 * pad - k) // stride + 1)
+    assert np.array_equal(got, ref)
+
+
+def test_maxpool_closed_forms():
+    # 1x1 windows: the identity.  A plane that increases along both axes: the
+    # maximum of a window is its last in-image corner, also at the borders.
+    x = _rand((1, 2, 5, 4), 25)
+    assert np.array_equal(oracle.maxpool2d(x, 1, 1, 0), x)
+    H = W = 8
+    ramp = (np.arange(H)[:, None] * 10.0 + np.arange(W)[None, :]).reshape(1, 1, H, W)
+    got = oracle.maxpool2d(-ramp, 3, 2, 1)      # all negative: a zero border would win
+    for oh in range(4):
+        for ow in range(4):
+            h0, w0 = max(2 * oh - 1, 0), max(2 * ow - 1, 0)
+            assert got[0, 0, oh, ow] == -(h0 * 10.0 + w0)
+    got = oracle.maxpool2d(ramp, 3, 2, 1)
+    for oh in range(4):
+        for ow in range(4):
+            h1, w1 = min(2 * oh + 1, H - 1), min(2 * ow + 1, W - 1)
+            assert got[0, 0, oh, ow] == h1 * 10.0 + w1
+
+
+@pytest.mark.parametrize("N,Cin,Cout,H,W,g,K,stride,pad", [
+    (2, 8, 12, 7, 6, 4, 3, 1, 1),
+    (1, 6, 6, 9, 9, 6, 3, 2, 1),
+    (2, 4, 8, 5, 5, 1, 1, 2, 0),
+    (1, 6, 4, 12, 11, 2, 7, 2, 3),
+])
+def test_channel_subset_is_a_slice_of_the_full_result(N, Cin, Cout, H, W, g, K, stride, pad):
+    # The sampled-channel routine (used at full batch sizes) must give exactly
+    # the planes the pinned full routine gives: same sum, same order.  Catches
+    # a wrong group for a selected filter, a selection / position mix-up,
+    # a border rule that differs from the full routine's.
+    x = _rand((N, Cin, H, W), 26)
+    w = _rand((Cout, Cin // g, K, K), 27)
+    full = oracle.conv2d_grouped(x, w, stride, pad, g)
+    for sel in ([Cout - 1, 0, Cout // 2], list(range(Cout)), [1, 1], [Cout // g - 1]):
+        sub = oracle.conv2d_grouped_channels(x, w, sel, stride, pad, g, threads=3)
+        assert np.array_equal(sub, full[:, sel])
+    with pytest.raises(ValueError):
+        oracle.conv2d_grouped_channels(x, w, [Cout], stride, pad, g)
+
+
+# --------------------------------------------------------------------------
+# The chain executor against a chain worked out by hand (tests/golden):
+# residual added before the ReLU, buffer routing, overwriting a buffer, the
+# stand-alone add / ReLU / max-pool steps.
+# --------------------------------------------------------------------------
+def _hand_chain():
+    from paper_2006_09791_amd.workloads import Layer
+    L = Layer
+    return [
+        L("conv", 0, -1, 1, 1, 2, 2, 2, 2, 1, 1, 1, 0, 2, True, 0),
+        L("conv", 1, 0, 2, 1, 2, 2, 2, 2, 1, 1, 1, 0, 1, True, 1),
+        L("maxpool", 2, -1, 3, 1, 2, 2, 2, 2, 3, 3, 2, 1, 1, False, -1),
+        L("add", 1, 2, 4, 1, 2, 2, 2, 2, 1, 1, 1, 0, 1, False, -1),
+        L("relu", 0, -1, 5, 1, 2, 2, 2, 2, 1, 1, 1, 0, 1, False, -1),
+        L("conv", 5, -1, 1, 1, 2, 2, 2, 2, 3, 3, 1, 1, 2, False, 2),
+    ]
+
+
+def test_run_chain_hand_example():
+    gold = _read_golden("chain_hand_example.txt")
+    x0 = np.array(gold["x0"]).reshape(1, 2, 2, 2)
+    weights = [np.array(gold["w1"]).reshape(2, 1, 1, 1), np.array(gold["w2"]).reshape(2, 2, 1, 1),
+               np.array(gold["w6"]).reshape(2, 1, 3, 3)]
+    layers = _hand_chain()
+    # after the first step buffer 1 holds step 1's result ...
+    first = oracle.run_chain(layers[:1], 6, x0, weights)
+    assert first[1].ravel().tolist() == gold["buf1_after_step1"]
+    assert all(first[i] is None for i in (2, 3, 4, 5))
+    # ... and at the end it holds step 6's
+    bufs = oracle.run_chain(layers, 6, x0, weights, threads=2)
+    assert bufs[0].ravel().tolist() == gold["x0"]
+    for i in (1, 2, 3, 4, 5):
+        assert bufs[i].ravel().tolist() == gold[f"buf{i}"], i
+    assert bufs[3].shape == (1, 2, 1, 1) and bufs[2].shape == (1, 2, 2, 2)
+
+
+def test_run_chain_add_with_relu_and_unknown_op():
+    from paper_2006_09791_amd.workloads import Layer
+    x0 = np.array([1.0, -5.0, 2.0, -1.0]).reshape(1, 1, 2, 2)
+    w = [np.array([-1.0]).reshape(1, 1, 1, 1)]
+    layers = [Layer("conv", 0, -1, 1, 1, 1, 2, 2, 1, 1, 1, 1, 0, 1, False, 0),     # -x
+              Layer("add", 0, 1, 2, 1, 1, 2, 2, 1, 1, 1, 1, 0, 1, True, -1),       # relu(x - x) = 0
+              Layer("add", 0, 0, 3, 1, 1, 2, 2, 1, 1, 1, 1, 0, 1, True, -1)]       # relu(2x)
+    bufs = oracle.run_chain(layers, 4, x0, w)
+    assert bufs[1].ravel().tolist() == [-1.0, 5.0, -2.0, 1.0]
+    assert bufs[2].ravel().tolist() == [0.0] * 4
+    assert bufs[3].ravel().tolist() == [2.0, 0.0, 4.0, 0.0]
+    with pytest.raises(ValueError):
+        oracle.run_chain([Layer("pool", 0, -1, 1, 1, 1, 2, 2, 1, 1, 1, 1, 0, 1, False, -1)], 2, x0, w)
 
 
 def test_bad_arguments_rejected():
