@@ -133,6 +133,7 @@ int prepare_conv(const void *input, const gspc_packed_t *pw, int N, int Cin, int
     p->wx = pw->geom.wino_bytes
                 ? reinterpret_cast<const float *>(static_cast<const char *>(pw->dev) + pw->geom.wino_offset)
                 : nullptr;
+    p->wr = pw->geom.row_bytes ? static_cast<const char *>(pw->dev) + pw->geom.row_offset : nullptr;
     p->y = static_cast<float *>(output);
     p->res = nullptr;
     p->N = N; p->Cin = Cin; p->H = H; p->W = W; p->Cout = Cout; p->KH = KH; p->KW = KW;
@@ -221,14 +222,41 @@ PackGeom make_pack_geom(int Cin, int Cout, int KH, int KW, int groups, int dtype
     }
     g.mfma_offset = (g.direct_bytes + 255) / 256 * 256;
     g.bf16_offset = (g.mfma_offset + g.mfma_bytes + 255) / 256 * 256;
-    if (dtype == GSPC_BF16 && KH == 3 && KW == 3 && g.KPG % 4 == 0 && g.CPG % 8 == 0) {
-        g.ckb = g.CPG % 32 == 0 ? 32 : g.CPG % 16 == 0 ? 16 : 8;
-        g.nchunks_b = g.CPG / g.ckb;
-        g.ks_b = (9 * g.ckb / 8 + 3) / 4;
-        g.mtiles_b = (g.KPG + 15) / 16;   // filter tiles, the last one zero-padded
-        g.bf16_bytes = (size_t)groups * g.nchunks_b * g.ks_b * g.mtiles_b * 1024;
+    if (dtype == GSPC_BF16 && KH == 3 && KW == 3) {
+        // 16x16x32 section: merge groups until a group has a multiple of 8 channels and of 4 filters
+        // (block-diagonal weights); `GSPC_MERGE_B` (measurement aid) asks for wider merged groups.
+        static const char *menv = std::getenv("GSPC_MERGE_B");
+        const int want_c = menv ? std::atoi(menv) : 8;
+        int m = 1;
+        while (m < 8 && groups % (2 * m) == 0 && ((g.CPG * m) % 8 || (g.KPG * m) % 4 || g.CPG * m < want_c)) m *= 2;
+        if ((g.CPG * m) % 8 == 0 && (g.KPG * m) % 4 == 0) {
+            g.mb = m;
+            g.gb = groups / m;
+            g.CPGb = g.CPG * m;
+            g.KPGb = g.KPG * m;
+            g.ckb = g.CPGb % 32 == 0 ? 32 : g.CPGb % 16 == 0 ? 16 : 8;
+            g.nchunks_b = g.CPGb / g.ckb;
+            g.ks_b = (9 * g.ckb / 8 + 3) / 4;
+            g.mtiles_b = (g.KPGb + 15) / 16;   // filter tiles, the last one zero-padded
+            g.bf16_bytes = (size_t)g.gb * g.nchunks_b * g.ks_b * g.mtiles_b * 1024;
+        }
     }
     g.total_bytes = g.bf16_bytes ? g.bf16_offset + g.bf16_bytes : g.mfma_offset + g.mfma_bytes;
+    if (dtype == GSPC_BF16 && KH == 3 && KW == 3) {
+        // row-product section: merged groups of 8 channels (16 where a group has 16 of its own)
+        int m = 1;
+        while (m < 8 && groups % (2 * m) == 0 && g.CPG * m < 8) m *= 2;
+        const int c = g.CPG * m, k = g.KPG * m;
+        if ((c == 8 || c == 16) && k % 4 == 0 && k <= 64) {
+            g.mt = m;
+            g.gt = groups / m;
+            g.CPGt = c;
+            g.KPGt = k;
+            g.row_offset = (g.total_bytes + 255) / 256 * 256;
+            g.row_bytes = (size_t)g.gt * (k / 4) * 3 * (c / 4) * 1024;
+            g.total_bytes = g.row_offset + g.row_bytes;
+        }
+    }
     if (dtype == GSPC_F32 && KH == 3 && KW == 3 && g.KPG >= 12 && g.CPG % 4 == 0 && g.CPG >= 8) {
         g.wino_offset = (g.total_bytes + 255) / 256 * 256;
         g.wino_bytes = (size_t)groups * (g.CPG / 4) * ((g.KPG + 15) / 16) * 4096;

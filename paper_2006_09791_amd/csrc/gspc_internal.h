@@ -45,8 +45,20 @@ struct PackGeom {
     // covers ckb input channels; its reduction is cut into units of 8 channels
     // at one tap, unit u = tap*(ckb/8) + channel block; lane l of k-step s holds
     // unit 4*s + l/16 of filter l%16 (zeros past the last unit).
+    // Layers with fewer than 8 channels per group reach this section by merging mb
+    // consecutive groups into one block-diagonal group (gb = groups / mb groups of CPGb = mb * CPG
+    // channels and KPGb = mb * KPG filters; weights between channels and filters of different
+    // original groups are zero, which is what Section II's definition of G(g) says they are).
     int ckb, ks_b, nchunks_b, mtiles_b;
+    int mb, gb, CPGb, KPGb;
     size_t bf16_bytes, bf16_offset;
+    // Row-product section (GSPC_BF16 handles, 3x3, merged groups of CPGt in {8, 16} channels and
+    // KPGt % 4 == 0 filters, mt original groups each): bf16 [gt][KPGt/4][3 kh][CPGt/4][64 lanes][8],
+    // the banded A operand of one v_mfma_f32_16x16x32_bf16: lane l, element e holds
+    // w[filter 4*fq + (l%16)/4][channel 4*cq + l/16][kh][kw = e - (l%16)%4 - 1], zero outside 0..2
+    // (rowb_kernels.hip).
+    int mt, gt, CPGt, KPGt;
+    size_t row_bytes, row_offset;
     // Winograd F(2x2, 3x3) section (GSPC_F32 handles, 3x3, KPG >= 12, CPG % 4 == 0,
     // CPG >= 8): fp32 U = G g G^T as [g][CPG/4][ceil(KPG/16)][4][64 lanes][4] (filters
     // past KPG in the last tile are zero); lane l holds
@@ -77,6 +89,7 @@ struct ConvParams {
     const float *wm;    // mfma section (nullptr if none)
     const void *wb;     // bf16 mfma section (nullptr if none)
     const float *wx;    // Winograd section (nullptr if none)
+    const void *wr;     // bf16 row-product section (nullptr if none)
     float *y;           // [N][Cout][Hout][Wout]
     const float *res;   // optional residual, same shape as y
     int N, Cin, H, W, Cout, KH, KW, stride, pad, groups;
@@ -106,6 +119,14 @@ struct MfmaB16Plan {
 bool plan_mfma_bf16(const ConvParams &p, const PackGeom &g, MfmaB16Plan *out);
 hipError_t launch_mfma_bf16(const ConvParams &p, const PackGeom &g, const MfmaB16Plan &plan, hipStream_t s,
                             const char **name);
+
+// bf16 row-product kernel for few channels per group (rowb_kernels.hip).
+struct RowB16Plan {
+    int inst;
+    int data[32];
+};
+bool plan_row_bf16(const ConvParams &p, const PackGeom &g, RowB16Plan *out);
+hipError_t launch_row_bf16(const ConvParams &p, const RowB16Plan &plan, hipStream_t s, const char **name);
 
 // 16x16x4 MFMA kernel with the filter tile resident in LDS (3x3, fp32 input).
 struct Mfma16wPlan {

@@ -685,11 +685,12 @@ struct PlanKeyHash {
     }
 };
 struct Plan {
-    int kind;  // 0 none, 32 (bf16), 64 (Winograd), 17 (resident filters), 16, 4
+    int kind;  // 0 none, 32 (bf16), 33 (bf16 row products), 64 (Winograd), 17 (resident filters), 16, 4
     int idx;
     Tile16 t16;
     Mfma4Plan p4;
     MfmaB16Plan pb;
+    RowB16Plan pr;
     Mfma16wPlan pw;
     WinoPlan px;
 };
@@ -697,12 +698,13 @@ struct Plan {
 const Plan &get_plan(const ConvParams &p, const PackGeom &g) {
     thread_local std::unordered_map<PlanKey, Plan, PlanKeyHash> cache;
     PlanKey k{{p.N, p.Cin, p.H, p.W, p.Cout, p.KH, p.KW, p.stride, p.pad, p.groups, p.in_bf16,
-               g.variant, p.wm != nullptr, p.wb != nullptr, winograd_mode()}};
+               g.variant, p.wm != nullptr, (p.wb != nullptr) + 2 * (p.wr != nullptr), winograd_mode()}};
     auto it = cache.find(k);
     if (it != cache.end()) return it->second;
     Plan pl{};
     const char fam = tuned_family(p);   // offline tile table: may prefer the plain 16x16x4 kernel
-    if (plan_mfma_bf16(p, g, &pl.pb)) pl.kind = 32;
+    if ((fam == '\0' || fam == 'r') && plan_row_bf16(p, g, &pl.pr)) pl.kind = 33;
+    else if (plan_mfma_bf16(p, g, &pl.pb)) pl.kind = 32;
     else if ((winograd_mode() != 0 || fam == 'x') && (fam == 'x' || fam == '\0') &&
              plan_wino(p, g, winograd_mode() < 0 && fam != 'x', &pl.px))
         pl.kind = 64;
@@ -731,6 +733,7 @@ hipError_t launch_mfma(const ConvParams &p, const PackGeom &g, hipStream_t s, co
         return p.in_bf16 ? launch16_cfg<uint16_t>(pl.idx, p, pl.t16, s) : launch16_cfg<float>(pl.idx, p, pl.t16, s);
     }
     if (pl.kind == 32) return launch_mfma_bf16(p, g, pl.pb, s, name);
+    if (pl.kind == 33) return launch_row_bf16(p, pl.pr, s, name);
     if (pl.kind == 64) return launch_wino(p, pl.px, s, name);
     if (pl.kind == 17) return launch_mfma16w(p, pl.pw, s, name);
     if (pl.kind == 4) return launch_mfma4(p, pl.p4, s, name);

@@ -538,7 +538,19 @@ hipError_t launchB_s(int ckb, int vw, const ConvParams &p, const TileB &t, hipSt
 
 }  // namespace
 
-bool plan_mfma_bf16(const ConvParams &p, const PackGeom &g, MfmaB16Plan *out) {
+// The layer as the 16x16x32 section sees it: merged groups (block-diagonal weights).
+static ConvParams merged_view(const ConvParams &p0, const PackGeom &g) {
+    ConvParams p = p0;
+    if (g.bf16_bytes) {
+        p.groups = g.gb;
+        p.CPG = g.CPGb;
+        p.KPG = g.KPGb;
+    }
+    return p;
+}
+
+bool plan_mfma_bf16(const ConvParams &p0, const PackGeom &g, MfmaB16Plan *out) {
+    const ConvParams p = merged_view(p0, g);
     if (!p.in_bf16 || !p.wb || !g.bf16_bytes || p.KH != 3 || p.KW != 3 || (p.stride != 1 && p.stride != 2))
         return false;
     static const char *force = std::getenv("GSPC_TILEB");
@@ -572,15 +584,17 @@ bool plan_mfma_bf16(const ConvParams &p, const PackGeom &g, MfmaB16Plan *out) {
     return true;
 }
 
-hipError_t launch_mfma_bf16(const ConvParams &p, const PackGeom &g, const MfmaB16Plan &plan, hipStream_t s,
+hipError_t launch_mfma_bf16(const ConvParams &p0, const PackGeom &g, const MfmaB16Plan &plan, hipStream_t s,
                             const char **name) {
+    const ConvParams p = merged_view(p0, g);
     TileB t;
     std::memcpy(&t, plan.data, sizeof(t));
     const CfgB &c = kCfgB[plan.inst];
     const int vw = vw_of(p.W);
     *name = intern_name("conv_mfma16b<" + std::to_string(c.MI) + "," + std::to_string(c.NI) + "," +
                         std::to_string(c.WM) + "," + std::to_string(c.WP) + "," + std::to_string(p.stride) + "," +
-                        std::to_string(g.ckb) + "," + std::to_string(vw) + (t.vec_out ? ",true>" : ",false>"));
+                        std::to_string(g.ckb) + "," + std::to_string(vw) + (t.vec_out ? ",true>" : ",false>") +
+                        (g.mb > 1 ? "/merge" + std::to_string(g.mb) : ""));
     switch (plan.inst) {
     case 0: return launchB_s<2, 4, 1, 4>(g.ckb, vw, p, t, s);
     case 1: return launchB_s<1, 4, 1, 4>(g.ckb, vw, p, t, s);

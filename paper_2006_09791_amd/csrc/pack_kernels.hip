@@ -95,16 +95,25 @@ __global__ void pack_wino_kernel(const float *__restrict__ w, float *__restrict_
     out[d] = u;
 }
 
-// bf16 matrix-core section, one thread per 2-byte element.
+// Weight of filter fo and channel cm of a merged group (m consecutive groups seen as one
+// block-diagonal group): zero unless both belong to the same original group.
+__device__ __forceinline__ float merged_weight(const float *__restrict__ w, const PackArgs &a, int m, int jm, int fo,
+                                               int cm, int tap) {
+    if (fo >= a.KPG * m || cm >= a.CPG * m || fo / a.KPG != cm / a.CPG) return 0.f;
+    const int oc = jm * a.KPG * m + fo;
+    return w[(size_t)oc * a.Kred + (size_t)(cm % a.CPG) * 9 + tap];
+}
+
+// bf16 matrix-core section, one thread per 2-byte element; m = groups merged per section group.
 __global__ void pack_bf16_kernel(const float *__restrict__ w, uint16_t *__restrict__ out, PackArgs a,
-                                 int ckb, int ks_b, int nchunks, size_t total) {
+                                 int ckb, int ks_b, int nchunks, int m, size_t total) {
     size_t d = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (d >= total) return;
     const int e = (int)(d % 8);
     size_t r = d / 8;
     const int lane = (int)(r % 64);
     r /= 64;
-    const int mtiles = (a.KPG + 15) / 16;
+    const int mtiles = (a.KPG * m + 15) / 16;
     const int mt = (int)(r % mtiles);
     r /= mtiles;
     const int ks = (int)(r % ks_b);
@@ -113,12 +122,37 @@ __global__ void pack_bf16_kernel(const float *__restrict__ w, uint16_t *__restri
     const int j = (int)(r / nchunks);
     const int u8 = ckb / 8, u = 4 * ks + lane / 16;
     uint16_t v = 0;
-    if (u < 9 * u8 && mt * 16 + lane % 16 < a.KPG) {
+    if (u < 9 * u8) {
         const int tap = u / u8, cb8 = u % u8;
-        const int c = chunk * ckb + cb8 * 8 + e;
-        const int oc = j * a.KPG + mt * 16 + lane % 16;
-        v = (uint16_t)(__float_as_uint(round_bf16(w[(size_t)oc * a.Kred + (size_t)c * 9 + tap])) >> 16);
+        v = (uint16_t)(__float_as_uint(round_bf16(merged_weight(w, a, m, j, mt * 16 + lane % 16,
+                                                                 chunk * ckb + cb8 * 8 + e, tap))) >> 16);
     }
+    out[d] = v;
+}
+
+// bf16 row-product section: banded operands [merged group][filter quad][kh][channel quad][lane][8].
+__global__ void pack_row_kernel(const float *__restrict__ w, uint16_t *__restrict__ out, PackArgs a, int m,
+                                size_t total) {
+    size_t d = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (d >= total) return;
+    const int e = (int)(d % 8);
+    size_t r = d / 8;
+    const int lane = (int)(r % 64);
+    r /= 64;
+    const int cqs = a.CPG * m / 4, fqs = a.KPG * m / 4;
+    const int cq = (int)(r % cqs);
+    r /= cqs;
+    const int kh = (int)(r % 3);
+    r /= 3;
+    const int fq = (int)(r % fqs);
+    const int j = (int)(r / fqs);
+    // product row (lane % 16) = (filter of the quad, output column of the window); reduction slot
+    // (lane / 16, e) = (channel of the quad, input column of the window); the window starts two
+    // columns left of its first output column
+    const int f = (lane % 16) / 4, ow = (lane % 16) % 4, kw = e - ow - 1;
+    uint16_t v = 0;
+    if (kw >= 0 && kw < 3)
+        v = (uint16_t)(__float_as_uint(round_bf16(merged_weight(w, a, m, j, fq * 4 + f, cq * 4 + lane / 16, kh * 3 + kw))) >> 16);
     out[d] = v;
 }
 
@@ -176,7 +210,14 @@ hipError_t launch_pack_weights(const float *w, const gspc_packed *h, hipStream_t
         uint16_t *bsec = reinterpret_cast<uint16_t *>(static_cast<char *>(h->dev) + h->geom.bf16_offset);
         const size_t nb = h->geom.bf16_bytes / 2;
         hipLaunchKernelGGL(pack_bf16_kernel, dim3(blocks_for(nb, 256)), dim3(256), 0, s, w, bsec, a,
-                           h->geom.ckb, h->geom.ks_b, h->geom.nchunks_b, nb);
+                           h->geom.ckb, h->geom.ks_b, h->geom.nchunks_b, h->geom.mb, nb);
+        e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    if (h->geom.row_bytes) {
+        uint16_t *rsec = reinterpret_cast<uint16_t *>(static_cast<char *>(h->dev) + h->geom.row_offset);
+        const size_t nr = h->geom.row_bytes / 2;
+        hipLaunchKernelGGL(pack_row_kernel, dim3(blocks_for(nr, 256)), dim3(256), 0, s, w, rsec, a, h->geom.mt, nr);
         e = hipGetLastError();
         if (e != hipSuccess) return e;
     }

@@ -7,7 +7,7 @@
 // Format: one layer per line, '#' starts a comment:
 //   N Cin H W Cout KH KW stride pad groups dtype family index
 // dtype 0 = fp32, 1 = bf16; family 'w' = 16x16x4 kernel with resident filters, 'm' = 16x16x4
-// kernel, 'b' = bf16 16x16x32 kernel, 'q' = 4x4x1 kernel, 'x' = Winograd F(2x2, 3x3) kernel; index = position in that family's
+// kernel, 'b' = bf16 16x16x32 kernel, 'q' = 4x4x1 kernel, 'x' = Winograd F(2x2, 3x3) kernel, 'r' = bf16 row-product kernel; index = position in that family's
 // configuration list (for 'q': pixel runs per wave, 1 | 2 | 4).  Entries that a planner cannot
 // realise are ignored (the heuristic choice is used).
 #include <array>
@@ -47,7 +47,7 @@ void load_table() {
         if (std::sscanf(line, "%d %d %d %d %d %d %d %d %d %d %d %c %d", &k[0], &k[1], &k[2], &k[3], &k[4], &k[5],
                         &k[6], &k[7], &k[8], &k[9], &k[10], &fam, &idx) != 13)
             continue;
-        if ((fam == 'w' || fam == 'm' || fam == 'b' || fam == 'q' || fam == 'x') && idx >= 0) g_table[k] = Entry{fam, idx};
+        if ((fam == 'w' || fam == 'm' || fam == 'b' || fam == 'q' || fam == 'x' || fam == 'r') && idx >= 0) g_table[k] = Entry{fam, idx};
     }
     std::fclose(f);
 }

@@ -200,6 +200,94 @@ def test_bf16_layers(gpu, s):
         assert rel_err(y, ref) < TOL_BF16, name
 
 
+# bf16 layers with few channels per group: the row-product kernel (groups of fewer than 8
+# channels are merged into block-diagonal groups of 8 by the pack step).
+ROW_BF16 = [
+    S(2, 64, 56, 56, 64, 3, 3, 1, 1, 8),      # 8 channels, 8 filters per group; 14 windows per row
+    S(3, 64, 56, 56, 64, 3, 3, 1, 1, 32),     # 2 and 2: four groups merged
+    S(5, 128, 28, 28, 128, 3, 3, 1, 1, 32),   # 4 and 4: two groups merged; two images per wave, odd batch
+    S(3, 128, 28, 28, 128, 3, 3, 1, 1, 8),    # 16 and 16: two waves share a group's input
+    S(2, 16, 12, 12, 32, 3, 3, 1, 1, 2),      # 8 channels, 16 filters; three windows per row, four images per wave
+    S(9, 8, 9, 8, 8, 3, 3, 1, 1, 8),          # depthwise, all eight groups merged; two windows per row
+    S(2, 32, 7, 64, 32, 3, 3, 1, 1, 4),       # sixteen windows per row, fewer rows than a band
+    S(1, 16, 40, 20, 24, 3, 3, 1, 1, 2),      # 12 filters per group: three filter quads
+    S(3, 48, 16, 16, 48, 3, 3, 1, 1, 3),      # 16 and 16, three groups
+    S(1, 24, 33, 36, 24, 3, 3, 1, 1, 12),     # 2 and 2, twelve groups in three merged ones; odd height
+]
+
+
+@pytest.mark.parametrize("s", ROW_BF16, ids=lambda s: "x".join(map(str, s)))
+def test_bf16_row_kernel(gpu, s):
+    torch, b = gpu
+    y, x, w, name = run_conv(gpu, s, seed=33, dtype=b.GSPC_BF16)
+    assert name.startswith("conv_row16b<"), name
+    assert not np.isnan(y).any(), name
+    _, xr = wl.round_to_bf16(x)
+    _, wr = wl.round_to_bf16(w)
+    ref_r = oracle.conv2d_grouped(xr, wr, s.stride, s.pad, s.groups, threads=8)
+    assert rel_err(y, ref_r) < 1e-4, name
+    ref = oracle.conv2d_grouped(x, w, s.stride, s.pad, s.groups, threads=8)
+    assert rel_err(y, ref) < TOL_BF16, name
+
+
+@pytest.mark.parametrize("bands", ["1", "3", "8"])
+def test_bf16_row_kernel_bands(gpu, bands):
+    """Row bands (each re-reads one row of its neighbours above and below) must tile the
+    plane exactly, also when the band height does not divide the plane."""
+    torch, b = gpu
+    import subprocess, sys, os, textwrap
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    code = textwrap.dedent(f"""
+        import sys, numpy as np
+        sys.path.insert(0, {root!r}); sys.path.insert(0, {os.path.join(root, "tests")!r})
+        import torch, oracle
+        from paper_2006_09791_amd import binding as b, workloads as wl
+        from helpers import rel_err
+        s = wl.ConvShape(3, 32, 26, 24, 32, 3, 3, 1, 1, 8)
+        x = wl.make_input((s.N, s.Cin, s.H, s.W), 5); w = wl.make_weight(s.Cout, s.Cin // s.groups, 3, 3, 6)
+        pw = b.gspc_pack_weights(torch.from_numpy(w).cuda(), s.groups, b.GSPC_BF16)
+        xd = b.gspc_pack_input_bf16(torch.from_numpy(x).cuda())
+        y = torch.full((s.N, s.Cout, s.H, s.W), float("nan"), device="cuda")
+        b.gspc_conv2d_grouped(xd, pw, s.N, s.Cin, s.H, s.W, s.Cout, 3, 3, 1, 1, s.groups, y)
+        torch.cuda.synchronize()
+        _, xr = wl.round_to_bf16(x); _, wr = wl.round_to_bf16(w)
+        err = rel_err(y.cpu().numpy(), oracle.conv2d_grouped(xr, wr, 1, 1, s.groups, threads=8))
+        print(b.gspc_last_kernel(), err < 1e-4)
+    """)
+    env = dict(os.environ, GSPC_ROWB_BANDS=bands)
+    out = subprocess.run([sys.executable, "-c", code], env=env, check=True, capture_output=True, text=True).stdout
+    line = [l for l in out.strip().splitlines() if l.startswith("conv_")][-1]
+    assert line.startswith("conv_row16b<") and line.endswith("True"), out
+    assert f"/{bands}b" in line.replace("/7b", "/8b"), out   # 8 bands of 4 rows: the 26 rows need 7
+
+
+def test_bf16_row_kernel_with_residual_and_relu(gpu):
+    """Epilogue form of the row-product kernel in a chain: conv + residual + ReLU, whole tensors."""
+    torch, b = gpu
+    from helpers import gpu_chain, oracle_chain
+    N, C, hw, g = 3, 64, 28, 16
+    ch = wl.Chain("rowres", (N, C, hw, hw))
+    ch.conv(0, 1, N, C, hw, hw, C, 3, 1, 1, g, relu=True)
+    ch.conv(0, 2, N, C, hw, hw, C, 3, 1, 1, g, relu=True, residual=1)
+    ch.conv(0, 3, N, C, hw, hw, C, 3, 1, 1, g, residual=2)
+    x0 = wl.make_input(ch.input_shape, 43)
+    _, x0r = wl.round_to_bf16(x0)
+    weights = [wl.round_to_bf16(w)[1] for w in ch.make_weights(11)]
+    dev = torch.device("cuda:0")
+    b.gspc_set_stream()
+    packed = [b.gspc_pack_weights(torch.from_numpy(w).to(dev), g, b.GSPC_BF16) for w in weights]
+    xd = b.gspc_pack_input_bf16(torch.from_numpy(x0).to(dev))
+    ref = oracle_chain(ch, x0r, weights, threads=8)
+    # every layer reads the bf16 input (buffer 0) and writes fp32: run them one by one
+    bufs = [xd] + [torch.full((N * C * hw * hw,), float("nan"), device=dev) for _ in range(3)]
+    for li, l in enumerate(ch.layers):
+        b.gspc_run_layer_chain(b.LayerChain([l._replace(wid=0)], [packed[li]], bufs))
+        torch.cuda.synchronize()
+        assert b.gspc_last_kernel().startswith("conv_row16b<"), b.gspc_last_kernel()
+        got = bufs[l.dst].cpu().numpy().reshape(ref[l.dst].shape)
+        assert rel_err(got, ref[l.dst]) < 1e-4, li
+
+
 def test_rerun_is_bit_identical(gpu):
     s = wl.wrn_grouped_shapes(2, 2)[2]
     y1, *_ = run_conv(gpu, s, seed=31)
