@@ -224,9 +224,11 @@ PackGeom make_pack_geom(int Cin, int Cout, int KH, int KW, int groups, int dtype
     g.bf16_offset = (g.mfma_offset + g.mfma_bytes + 255) / 256 * 256;
     if (dtype == GSPC_BF16 && KH == 3 && KW == 3) {
         // 16x16x32 section: merge groups until a group has a multiple of 8 channels and of 4 filters
-        // (block-diagonal weights); `GSPC_MERGE_B` (measurement aid) asks for wider merged groups.
+        // and at least 16 channels (block-diagonal weights: a half-empty filter tile and a reduction
+        // of 72 padded to 96 cost more than the idle multiplications; 256 -> 256 on 14x14 at batch
+        // 256, g = 32: 25.8 -> 20.5 us).  `GSPC_MERGE_B` (measurement aid) sets another width.
         static const char *menv = std::getenv("GSPC_MERGE_B");
-        const int want_c = menv ? std::atoi(menv) : 8;
+        const int want_c = menv ? std::atoi(menv) : 16;
         int m = 1;
         while (m < 8 && groups % (2 * m) == 0 && ((g.CPG * m) % 8 || (g.KPG * m) % 4 || g.CPG * m < want_c)) m *= 2;
         if ((g.CPG * m) % 8 == 0 && (g.KPG * m) % 4 == 0) {

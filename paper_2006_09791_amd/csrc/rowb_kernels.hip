@@ -208,6 +208,207 @@ __global__ __launch_bounds__(256, OCC) void conv_row16b(ConvParams p, TileR t) {
     }
 }
 
+// 4x4 transpose between four registers and the four 16-lane rows of a wavefront:
+// afterwards register i, row r holds what register r, row i held.  v_permlane16_swap
+// exchanges the odd rows of its first operand with the even rows of its second,
+// v_permlane32_swap the upper half of the first with the lower half of the second.
+__device__ __forceinline__ void transpose_rows(unsigned &a0, unsigned &a1, unsigned &a2, unsigned &a3) {
+    const auto p01 = __builtin_amdgcn_permlane16_swap(a0, a1, false, false);
+    const auto p23 = __builtin_amdgcn_permlane16_swap(a2, a3, false, false);
+    const auto q02 = __builtin_amdgcn_permlane32_swap(p01[0], p23[0], false, false);
+    const auto q13 = __builtin_amdgcn_permlane32_swap(p01[1], p23[1], false, false);
+    a0 = q02[0];
+    a2 = q02[1];
+    a1 = q13[0];
+    a3 = q13[1];
+}
+template <typename V> __device__ __forceinline__ void transpose_rows4(V &a0, V &a1, V &a2, V &a3) {
+    u32x4 b0 = __builtin_bit_cast(u32x4, a0), b1 = __builtin_bit_cast(u32x4, a1), b2 = __builtin_bit_cast(u32x4, a2),
+          b3 = __builtin_bit_cast(u32x4, a3);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        unsigned c0 = b0[e], c1 = b1[e], c2 = b2[e], c3 = b3[e];
+        transpose_rows(c0, c1, c2, c3);
+        b0[e] = c0;
+        b1[e] = c1;
+        b2[e] = c2;
+        b3[e] = c3;
+    }
+    a0 = __builtin_bit_cast(V, b0);
+    a1 = __builtin_bit_cast(V, b1);
+    a2 = __builtin_bit_cast(V, b2);
+    a3 = __builtin_bit_cast(V, b3);
+}
+
+// The same row products with memory touched four rows at a time.  conv_row16b asks for one
+// row of four channels per load and writes one row of four filters per store: pieces of 2*W
+// and 4*W bytes, each in a different plane.  Here a load instruction fetches four consecutive
+// rows of ONE channel (lane group = row: 8*W contiguous bytes) and a store instruction writes
+// four consecutive rows of ONE filter (16*W contiguous bytes); a 4x4 exchange between
+// registers and lane groups (transpose_rows) turns four such loads into the four channels x
+// one row operands the products want, and four finished output rows back into the store
+// layout.  A trip of the loop is eight steps: two input quads, two output quads, eight
+// accumulator sets (output row r lives in set r % 8).
+template <int CQ, int FQ, bool EPI>
+__global__ __launch_bounds__(256, 2) void conv_row16q(ConvParams p, TileR t) {
+    const int lane = threadIdx.x & 63;
+    const unsigned wi = blockIdx.x * 4 + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    if (wi >= t.items) return;   // uniform over the wave; the kernel has no barriers
+    const unsigned q1 = fast_div(wi, t.m_FS);
+    const int fs = wi - q1 * t.FS;
+    const unsigned q2 = fast_div(q1, t.m_bands);
+    const int band = q1 - q2 * t.bands;
+    const unsigned is = fast_div(q2, t.m_gt);
+    const int j = q2 - is * t.gt;
+    const int oh0 = band * t.TH;
+    const int oh1 = oh0 + t.TH < p.H ? oh0 + t.TH : p.H;
+    const int rows = oh1 - oh0, nsteps = rows + 2;   // input rows oh0 - 1 .. oh1
+    const int ntrips = (4 * ((rows + 3) / 4) + 2 + 7) / 8;
+
+    const __amdgpu_buffer_rsrc_t rx = make_rsrc(p.x, t.x_bytes);
+    const __amdgpu_buffer_rsrc_t rw = make_rsrc(p.wr, t.w_bytes);
+    const __amdgpu_buffer_rsrc_t ry = make_rsrc(p.y, t.y_bytes);
+    const __amdgpu_buffer_rsrc_t rr = make_rsrc(p.res ? p.res : p.y, t.y_bytes);
+
+    // Lane l: window slot l % 16 as in conv_row16b; lane group l / 16 is a row of the quad in
+    // memory instructions and a channel / filter of the quad in the products.
+    const int nslot = lane & 15, g4 = lane >> 4;
+    const int win = nslot & (t.WPR - 1);
+    const unsigned img = is * t.SPW + (nslot >> t.wpr_shift);
+    const bool live = win < t.nwin && img < (unsigned)p.N;
+    const bool is_first = win == 0, is_last = win == t.nwin - 1;
+    const unsigned HW = p.H * p.W;
+    const unsigned colb = is_first ? 0u : is_last ? (p.W - 8) * 2u : (win * 4 - 2) * 2u;
+    const unsigned xb = ((img * p.Cin + j * t.CPGt) * HW) * 2u + colb;
+    const unsigned yb = ((img * p.Cout + j * t.KPGt + fs * FQ * 4) * HW) * 4u + win * 16u;
+
+    bf16x8 A[FQ][3][CQ];
+    {
+        const unsigned abase = ((unsigned)(j * t.FQT + fs * FQ) * 3 * CQ * 64 + lane) * 16u;
+#pragma unroll
+        for (int fq = 0; fq < FQ; ++fq)
+#pragma unroll
+            for (int kh = 0; kh < 3; ++kh)
+#pragma unroll
+                for (int cq = 0; cq < CQ; ++cq)
+                    A[fq][kh][cq] = __builtin_bit_cast(
+                        bf16x8, __builtin_amdgcn_raw_buffer_load_b128(rw, abase, ((fq * 3 + kh) * CQ + cq) * 1024, 0));
+        __builtin_amdgcn_sched_barrier(0);   // see conv_row16b: the operands arrive before the first request
+#pragma unroll
+        for (int fq = 0; fq < FQ; ++fq)
+#pragma unroll
+            for (int kh = 0; kh < 3; ++kh)
+#pragma unroll
+                for (int cq = 0; cq < CQ; ++cq) asm volatile("" : "+v"(A[fq][kh][cq]));
+        __builtin_amdgcn_sched_barrier(0);
+    }
+
+    u32x4 L[2][4 * CQ];          // two input quads: [channel] with lane group = row until transposed
+    f32x4 R[EPI ? 4 * FQ : 1];   // residual of the output quad stored next, in store layout
+    f32x4 acc[8][FQ];
+#pragma unroll
+    for (int s = 0; s < 8; ++s)
+#pragma unroll
+        for (int fq = 0; fq < FQ; ++fq) acc[s][fq] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    // Input quad q: rows oh0 - 1 + 4q .. + 3, every channel of the merged group.
+    auto issue_quad = [&](int q, u32x4(&dst)[4 * CQ]) {
+        const int st = 4 * q + g4, row = oh0 - 1 + st;
+        const bool ok = live && st < nsteps && (unsigned)row < (unsigned)p.H;
+        const unsigned vo = ok ? xb + (unsigned)row * p.W * 2u : kOob;
+#pragma unroll
+        for (int c = 0; c < 4 * CQ; ++c) dst[c] = __builtin_amdgcn_raw_buffer_load_b128(rx, vo, c * HW * 2, 0);
+    };
+    // Output quad m: rows oh0 + 4m .. + 3 of this wave's filters (m = -1: nothing).
+    auto quad_offset = [&](int m) -> unsigned {
+        const int orow = 4 * m + g4;
+        return live && m >= 0 && orow < rows ? yb + (unsigned)(oh0 + orow) * p.W * 4u : kOob;
+    };
+    auto issue_res = [&](int m) {
+        if (!EPI) return;
+        const unsigned vo = p.res ? quad_offset(m) : kOob;
+#pragma unroll
+        for (int k = 0; k < 4 * FQ; ++k)
+            R[EPI ? k : 0] = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(rr, vo, k * HW * 4, 0));
+    };
+    auto store_quad = [&](int m, f32x4(&a0)[FQ], f32x4(&a1)[FQ], f32x4(&a2)[FQ], f32x4(&a3)[FQ]) {
+        const unsigned vo = quad_offset(m);
+#pragma unroll
+        for (int fq = 0; fq < FQ; ++fq) {
+            transpose_rows4(a0[fq], a1[fq], a2[fq], a3[fq]);   // register i: filter 4*fq + i, lane group = row
+            f32x4 *o[4] = {&a0[fq], &a1[fq], &a2[fq], &a3[fq]};
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                if (EPI) *o[i] += R[EPI ? fq * 4 + i : 0];
+                if (EPI && p.relu) {
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) (*o[i])[r] = fmaxf((*o[i])[r], 0.f);
+                }
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int fq = 0; fq < FQ; ++fq) {
+            const f32x4 *o[4] = {&a0[fq], &a1[fq], &a2[fq], &a3[fq]};
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, *o[i]), ry, vo, (fq * 4 + i) * HW * 4, 0);
+        }
+    };
+    // One step: the row in `raw` (lane group = channel) goes to the output row that starts here
+    // (set s_new, kh = 0), the one in its middle (kh = 1) and the one it completes (kh = 2).
+    auto step_fn = [&](const u32x4(&rowops)[4 * CQ], int r, f32x4(&a_new)[FQ], f32x4(&a_mid)[FQ], f32x4(&a_end)[FQ]) {
+#pragma unroll
+        for (int cq = 0; cq < CQ; ++cq) {
+            const u32x4 raw = rowops[4 * cq + r];
+            u32x4 b;
+            b.x = is_first ? 0u : is_last ? raw.y : raw.x;
+            b.y = is_first ? raw.x : is_last ? raw.z : raw.y;
+            b.z = is_first ? raw.y : is_last ? raw.w : raw.z;
+            b.w = is_first ? raw.z : is_last ? 0u : raw.w;
+            const bf16x8 bv = __builtin_bit_cast(bf16x8, b);
+#pragma unroll
+            for (int fq = 0; fq < FQ; ++fq) {
+                a_new[fq] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A[fq][0][cq], bv,
+                                                                    cq == 0 ? f32x4{0.f, 0.f, 0.f, 0.f} : a_new[fq], 0, 0, 0);
+                a_mid[fq] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A[fq][1][cq], bv, a_mid[fq], 0, 0, 0);
+                a_end[fq] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A[fq][2][cq], bv, a_end[fq], 0, 0, 0);
+            }
+        }
+    };
+
+    // Prologue in the shape of half a trip (requests, stores, residual requests), so that the
+    // loop's first wait sees the same queue on its way in as on its way round.
+    issue_quad(0, L[0]);
+    store_quad(-1, acc[4], acc[5], acc[6], acc[7]);
+    issue_res(-1);
+
+#pragma clang loop unroll(disable)
+    for (int T = 0; T < ntrips; ++T) {
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            __builtin_amdgcn_sched_barrier(0);
+            issue_quad(2 * T + 1 + h, L[1 - h]);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int cq = 0; cq < CQ; ++cq)
+                transpose_rows4(L[h][4 * cq], L[h][4 * cq + 1], L[h][4 * cq + 2], L[h][4 * cq + 3]);
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int u = 4 * h + r;
+                step_fn(L[h], r, acc[u], acc[(u + 7) % 8], acc[(u + 6) % 8]);
+                if (r == 1) {
+                    // rows 4 * (2T - 1 + h) .. + 3 are complete: sets 4..7 in the first half, 0..3 in the second
+                    __builtin_amdgcn_sched_barrier(0);
+                    store_quad(2 * T - 1 + h, acc[4 - 4 * h], acc[5 - 4 * h], acc[6 - 4 * h], acc[7 - 4 * h]);
+                    issue_res(2 * T + h);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            }
+        }
+    }
+}
+
 // ---------------------------------------------------------------------------
 // Host side.
 // ---------------------------------------------------------------------------
@@ -217,7 +418,9 @@ struct CfgR {
     int CQ, FQ, D, OCC;
 };
 // filter quads per wave are limited by the registers the banded operands take (12 * CQ * FQ)
-const CfgR kCfgR[] = {{2, 2, 4, 4}, {2, 4, 4, 2}, {2, 1, 4, 4}, {4, 2, 4, 2}, {4, 1, 4, 2}, {2, 2, 8, 2}};
+// D = 0: the four-rows-at-a-time form (conv_row16q)
+const CfgR kCfgR[] = {{2, 2, 4, 4}, {2, 4, 4, 2}, {2, 1, 4, 4}, {4, 2, 4, 2}, {4, 1, 4, 2}, {2, 2, 8, 2},
+                      {2, 2, 0, 2}, {2, 1, 0, 2}, {4, 1, 0, 2}};
 constexpr int kNumCfgR = sizeof(kCfgR) / sizeof(kCfgR[0]);
 
 template <int CQ, int FQ, int D, int OCC>
@@ -226,6 +429,15 @@ hipError_t launchR(const ConvParams &p, const TileR &t, hipStream_t s) {
         hipLaunchKernelGGL((conv_row16b<CQ, FQ, D, 2, true>), dim3((t.items + 3) / 4), dim3(256), 0, s, p, t);
     else
         hipLaunchKernelGGL((conv_row16b<CQ, FQ, D, OCC, false>), dim3((t.items + 3) / 4), dim3(256), 0, s, p, t);
+    return hipGetLastError();
+}
+
+template <int CQ, int FQ>
+hipError_t launchQ(const ConvParams &p, const TileR &t, hipStream_t s) {
+    if (p.res || p.relu)
+        hipLaunchKernelGGL((conv_row16q<CQ, FQ, true>), dim3((t.items + 3) / 4), dim3(256), 0, s, p, t);
+    else
+        hipLaunchKernelGGL((conv_row16q<CQ, FQ, false>), dim3((t.items + 3) / 4), dim3(256), 0, s, p, t);
     return hipGetLastError();
 }
 
@@ -240,9 +452,15 @@ bool plan_row_bf16(const ConvParams &p, const PackGeom &g, RowB16Plan *out) {
     static const char *force = std::getenv("GSPC_TILER");
     int inst = -1;
     const int forced = force ? std::atoi(force) : tuned_config(p, 'r');
-    for (int i = 0; i < kNumCfgR && inst < 0; ++i) {
+    // preference: four rows at a time (6, 7), then one row at a time; with 16 channels per group the
+    // one-row form with two filter quads per wave comes first (the four-row form has registers for
+    // one quad only and then four waves read the same input: 31 against 41 us on 128 -> 128, 28x28,
+    // g = 8 at batch 256); 5 (seven rows in flight) only on request
+    static const int order[] = {6, 7, 3, 8, 0, 1, 2, 4, 5};
+    for (int k = 0; k < kNumCfgR && inst < 0; ++k) {
+        const int i = order[k];
         if (forced >= 0 && forced != i) continue;
-        if (forced < 0 && i == 5) continue;   // the deep-prefetch variant only on request
+        if (forced < 0 && i == 5) continue;
         if (kCfgR[i].CQ == CQ && FQT % kCfgR[i].FQ == 0) inst = i;
     }
     if (inst < 0) return false;
@@ -290,8 +508,10 @@ hipError_t launch_row_bf16(const ConvParams &p, const RowB16Plan &plan, hipStrea
     TileR t;
     std::memcpy(&t, plan.data, sizeof(t));
     const CfgR &c = kCfgR[plan.inst];
-    *name = intern_name("conv_row16b<" + std::to_string(c.CQ) + "," + std::to_string(c.FQ) + "," + std::to_string(c.D) +
-                        "," + std::to_string(c.OCC) + ">/" + std::to_string(t.bands) + "b");
+    *name = c.D == 0 ? intern_name("conv_row16q<" + std::to_string(c.CQ) + "," + std::to_string(c.FQ) + ">/" +
+                                   std::to_string(t.bands) + "b")
+                     : intern_name("conv_row16b<" + std::to_string(c.CQ) + "," + std::to_string(c.FQ) + "," +
+                                   std::to_string(c.D) + "," + std::to_string(c.OCC) + ">/" + std::to_string(t.bands) + "b");
     switch (plan.inst) {
     case 0: return launchR<2, 2, 4, 4>(p, t, s);
     case 1: return launchR<2, 4, 4, 2>(p, t, s);
@@ -299,6 +519,9 @@ hipError_t launch_row_bf16(const ConvParams &p, const RowB16Plan &plan, hipStrea
     case 3: return launchR<4, 2, 4, 2>(p, t, s);
     case 4: return launchR<4, 1, 4, 2>(p, t, s);
     case 5: return launchR<2, 2, 8, 2>(p, t, s);
+    case 6: return launchQ<2, 2>(p, t, s);
+    case 7: return launchQ<2, 1>(p, t, s);
+    case 8: return launchQ<4, 1>(p, t, s);
     }
     return hipErrorNotSupported;
 }

@@ -220,7 +220,7 @@ ROW_BF16 = [
 def test_bf16_row_kernel(gpu, s):
     torch, b = gpu
     y, x, w, name = run_conv(gpu, s, seed=33, dtype=b.GSPC_BF16)
-    assert name.startswith("conv_row16b<"), name
+    assert name.startswith("conv_row16"), name
     assert not np.isnan(y).any(), name
     _, xr = wl.round_to_bf16(x)
     _, wr = wl.round_to_bf16(w)
@@ -230,11 +230,20 @@ def test_bf16_row_kernel(gpu, s):
     assert rel_err(y, ref) < TOL_BF16, name
 
 
-@pytest.mark.parametrize("bands", ["1", "3", "8"])
-def test_bf16_row_kernel_bands(gpu, bands):
-    """Row bands (each re-reads one row of its neighbours above and below) must tile the
-    plane exactly, also when the band height does not divide the plane."""
-    torch, b = gpu
+@pytest.mark.parametrize("env,expect", [
+    ({"GSPC_ROWB_BANDS": "1"}, "conv_row16q<2,2>/1b"),
+    ({"GSPC_ROWB_BANDS": "3"}, "conv_row16q<2,2>/3b"),
+    ({"GSPC_ROWB_BANDS": "8"}, "conv_row16q<2,2>/7b"),       # 8 bands of 4 rows: the 26 rows need 7
+    ({"GSPC_TILER": "0", "GSPC_ROWB_BANDS": "1"}, "conv_row16b<2,2,4,4>/1b"),   # the one-row-at-a-time form
+    ({"GSPC_TILER": "0", "GSPC_ROWB_BANDS": "3"}, "conv_row16b<2,2,4,4>/3b"),
+    ({"GSPC_TILER": "2"}, "conv_row16b<2,1,4,4>"),            # one filter quad per wave: two waves share the input
+    ({"GSPC_TILER": "7"}, "conv_row16q<2,1>"),
+    ({"GSPC_TILER": "5"}, "conv_row16b<2,2,8,2>"),            # seven rows in flight
+])
+def test_bf16_row_kernel_forms_and_bands(gpu, env, expect):
+    """Both forms of the row-product kernel, and row bands (each re-reads one row of its
+    neighbours above and below) that must tile the plane exactly, also when the band height
+    does not divide the plane.  The choice is made per process, hence the child process."""
     import subprocess, sys, os, textwrap
     root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
     code = textwrap.dedent(f"""
@@ -243,22 +252,22 @@ def test_bf16_row_kernel_bands(gpu, bands):
         import torch, oracle
         from paper_2006_09791_amd import binding as b, workloads as wl
         from helpers import rel_err
-        s = wl.ConvShape(3, 32, 26, 24, 32, 3, 3, 1, 1, 8)
-        x = wl.make_input((s.N, s.Cin, s.H, s.W), 5); w = wl.make_weight(s.Cout, s.Cin // s.groups, 3, 3, 6)
-        pw = b.gspc_pack_weights(torch.from_numpy(w).cuda(), s.groups, b.GSPC_BF16)
-        xd = b.gspc_pack_input_bf16(torch.from_numpy(x).cuda())
-        y = torch.full((s.N, s.Cout, s.H, s.W), float("nan"), device="cuda")
-        b.gspc_conv2d_grouped(xd, pw, s.N, s.Cin, s.H, s.W, s.Cout, 3, 3, 1, 1, s.groups, y)
-        torch.cuda.synchronize()
-        _, xr = wl.round_to_bf16(x); _, wr = wl.round_to_bf16(w)
-        err = rel_err(y.cpu().numpy(), oracle.conv2d_grouped(xr, wr, 1, 1, s.groups, threads=8))
-        print(b.gspc_last_kernel(), err < 1e-4)
+        for s in (wl.ConvShape(3, 32, 26, 24, 32, 3, 3, 1, 1, 8), wl.ConvShape(5, 16, 9, 12, 16, 3, 3, 1, 1, 8)):
+            x = wl.make_input((s.N, s.Cin, s.H, s.W), 5); w = wl.make_weight(s.Cout, s.Cin // s.groups, 3, 3, 6)
+            pw = b.gspc_pack_weights(torch.from_numpy(w).cuda(), s.groups, b.GSPC_BF16)
+            xd = b.gspc_pack_input_bf16(torch.from_numpy(x).cuda())
+            y = torch.full((s.N, s.Cout, s.H, s.W), float("nan"), device="cuda")
+            b.gspc_conv2d_grouped(xd, pw, s.N, s.Cin, s.H, s.W, s.Cout, 3, 3, 1, 1, s.groups, y)
+            torch.cuda.synchronize()
+            _, xr = wl.round_to_bf16(x); _, wr = wl.round_to_bf16(w)
+            err = rel_err(y.cpu().numpy(), oracle.conv2d_grouped(xr, wr, 1, 1, s.groups, threads=8))
+            print(b.gspc_last_kernel(), err < 1e-4)
     """)
-    env = dict(os.environ, GSPC_ROWB_BANDS=bands)
-    out = subprocess.run([sys.executable, "-c", code], env=env, check=True, capture_output=True, text=True).stdout
-    line = [l for l in out.strip().splitlines() if l.startswith("conv_")][-1]
-    assert line.startswith("conv_row16b<") and line.endswith("True"), out
-    assert f"/{bands}b" in line.replace("/7b", "/8b"), out   # 8 bands of 4 rows: the 26 rows need 7
+    out = subprocess.run([sys.executable, "-c", code], env=dict(os.environ, **env), check=True, capture_output=True,
+                         text=True).stdout
+    lines = [l for l in out.strip().splitlines() if l.startswith("conv_")]
+    assert len(lines) == 2 and all(l.endswith("True") for l in lines), out
+    assert lines[0].startswith(expect), out
 
 
 def test_bf16_row_kernel_with_residual_and_relu(gpu):
@@ -283,7 +292,7 @@ def test_bf16_row_kernel_with_residual_and_relu(gpu):
     for li, l in enumerate(ch.layers):
         b.gspc_run_layer_chain(b.LayerChain([l._replace(wid=0)], [packed[li]], bufs))
         torch.cuda.synchronize()
-        assert b.gspc_last_kernel().startswith("conv_row16b<"), b.gspc_last_kernel()
+        assert b.gspc_last_kernel().startswith("conv_row16"), b.gspc_last_kernel()
         got = bufs[l.dst].cpu().numpy().reshape(ref[l.dst].shape)
         assert rel_err(got, ref[l.dst]) < 1e-4, li
 
