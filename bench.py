@@ -83,6 +83,14 @@ def main():
     torch.cuda.set_stream(stream)
     b.gspc_set_stream()
 
+    if args.traffic_probe:
+        src = torch.ones(64 * 1024 * 1024, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            torch.mul(src, 1.0, out=dst)      # one elementwise kernel: reads and writes 256 MiB
+        torch.cuda.synchronize()
+        del src, dst
+
     if args.sweep:
         from paper_2006_09791_amd import layer_timing
         if args.sweep == "wrn":
@@ -170,8 +178,16 @@ def main():
             # depthwise 3x3 + pointwise 1x1 blocks, as two kernels and with chain fusion
             rows = layer_timing.time_blocks(wl.depthwise_pairs(256), inner=8, reps=5)
         elif args.sweep == "resnet_bf16":
+            # each layer twice: re-using one input and one output buffer (a working set of up to
+            # 308 MB, of which the 256 MB last-level cache keeps a part), and over a rotation of three
+            # buffer sets, so that every launch streams from and to HBM
             shapes = [s for g in (2, 8, 32) for s in wl.resnet34_grouped_shapes(256, g)]
             rows = layer_timing.time_layers(shapes, "bf16", inner=4, reps=5)
+            cold = layer_timing.time_layers(shapes, "bf16", inner=6, reps=4, rotate=3)
+            for r, c in zip(rows, cold):
+                r["us_rotating"] = c["us"]
+                r["gbs_rotating"] = c["gbs"]
+                r["frac_hbm_rotating"] = c["frac_hbm"]
         else:
             # batched re-run of the MobileNet-shaped depthwise layers; buffer sets
             # rotate so that every launch streams from HBM rather than from cache
@@ -179,14 +195,6 @@ def main():
             rows = layer_timing.time_layers(shapes, "f32", inner=8, reps=5, rotate=4)
         print(json.dumps({"sweep": args.sweep, "rows": rows}))
         return 0
-
-    if args.traffic_probe:
-        src = torch.ones(64 * 1024 * 1024, dtype=torch.float32, device=dev)
-        dst = torch.empty_like(src)
-        for _ in range(3):
-            torch.mul(src, 1.0, out=dst)      # one elementwise kernel: reads and writes 256 MiB
-        torch.cuda.synchronize()
-        del src, dst
 
     # ---- build the five chains, everything resident on the device ----------
     chains, lcs, keep = [], [], []
