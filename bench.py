@@ -12,7 +12,13 @@ Also reported on the same line:
                  algorithmic flops (or bytes) per launch over its average
                  launch duration, measured here with events on the launch
                  stream by running each of its layers back to back.
-  cpu_baseline - the CPU oracle timed on the host cores on a bounded sample.
+  roofline_hbm - the same for the HBM-bound side of the path: the MobileNet-shaped
+                 depthwise 3x3 layers at batch 256 over rotating buffers, dominant kernel.
+  latency_ms   - batch-1 latency of the WRN-40-2-style and ResNet-34-shaped networks
+                 for every g (the quantity of the paper's Tables II-III), recorded chains.
+  cpu_baseline - the CPU oracle timed on the host cores: all cores on the same batch,
+                 one thread on a smaller sample, and Algorithm 1 in its vectorised CPU
+                 schedule ("the paper's method on the host").
 """
 import argparse
 import json
@@ -49,6 +55,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-roofline", action="store_true")
+    ap.add_argument("--no-extra", action="store_true", help="skip the roofline_hbm and latency_ms legs")
     ap.add_argument("--traffic-probe", action="store_true",
                     help="first run a plain 256 MiB device copy three times: the known-size kernel "
                          "against which rocprofv3's FETCH_SIZE / WRITE_SIZE counters are scaled")
@@ -305,16 +312,75 @@ def main():
             roofline = {"bound": "mfma", "achieved": round(ach, 2), "peak": PEAK_F32_MFMA_TFLOPS,
                         "unit": "TFLOP/s", "frac": round(ach / PEAK_F32_MFMA_TFLOPS, 4)}
             if "wino" in name:
-                # algorithmic flops are those of the direct sum (Eq. 2); the Winograd kernel needs 16/36 of
-                # the multiplications, so this fraction is an effective rate, not matrix-core occupancy
+                # algorithmic flops are those of the direct sum (Eq. 2); the Winograd kernel executes 16/36 of
+                # the multiplications, so `frac` is an effective rate; `executed_frac` is the share of the
+                # matrix-core peak that the executed multiplications take
                 roofline["algorithm"] = "winograd F(2x2,3x3): executes 16/36 of the Eq. 2 multiplications"
+                roofline["executed_frac"] = round(ach * 16.0 / 36.0 / PEAK_F32_MFMA_TFLOPS, 4)
         else:
             ach = k["bytes"] / k["time"] / 1e9
             roofline = {"bound": "hbm", "achieved": round(ach, 1), "peak": PEAK_HBM_GBS,
                         "unit": "GB/s", "frac": round(ach / PEAK_HBM_GBS, 4)}
-        roofline.update({"traffic": traffic, "kernel": name, "launches_per_step": k["launches"],
+        traffic_at = None
+        if os.path.exists(TRAFFIC_FILE):
+            try:
+                traffic_at = json.load(open(TRAFFIC_FILE)).get("_measured_at")
+            except Exception:
+                pass
+        roofline.update({"traffic": traffic, "traffic_measured_at": traffic_at,
+                         "traffic_algorithmic": round(k["bytes"] / k["launches"]),
+                         "kernel": name, "launches_per_step": k["launches"],
                          "avg_launch_us": round(k["time"] / k["launches"] * 1e6, 2),
                          "share_of_step": round(k["time"] / sum(v["time"] for v in kernels.values()), 3)})
+        all_flops = sum(v["flops"] for v in kernels.values())
+        roofline["winograd_share_of_macs"] = round(sum(v["flops"] for n, v in kernels.items() if "wino" in n) / all_flops, 4)
+
+    # ---- HBM side: depthwise 3x3 layers at batch 256, rotating buffers ------------
+    roofline_hbm, latency = None, None
+    if not args.no_extra:
+        from paper_2006_09791_amd import layer_timing
+        b.gspc_set_stream(stream)
+        shapes = [dw for dw, _ in wl.depthwise_pairs(256)]
+        rows = layer_timing.time_layers(shapes, "f32", inner=8, reps=3, rotate=4)
+        fam = {}
+        for sh, r in zip(shapes, rows):
+            f = fam.setdefault(r["kernel"], {"time": 0.0, "bytes": 0.0, "launches": 0})
+            f["time"] += r["us"] * 1e-6
+            f["bytes"] += layer_timing.layer_bytes(sh, 4)
+            f["launches"] += 1
+        name, f = max(fam.items(), key=lambda kv: kv[1]["time"])
+        ach = f["bytes"] / f["time"] / 1e9
+        roofline_hbm = {"bound": "hbm", "achieved": round(ach, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                        "frac": round(ach / PEAK_HBM_GBS, 4), "traffic": None, "kernel": name,
+                        "workload": "MobileNet-shaped depthwise 3x3 layers (C, HxW) in {(32,112),(64,112),(128,56),(256,28),"
+                                    "(512,14),(1024,7)} x stride {1,2}, fp32, N=256, four rotating buffer sets",
+                        "layers_served": f["launches"], "avg_launch_us": round(f["time"] / f["launches"] * 1e6, 2),
+                        "all_layers_frac": round(sum(v["bytes"] for v in fam.values()) / sum(v["time"] for v in fam.values())
+                                                 / 1e9 / PEAK_HBM_GBS, 4)}
+
+        # ---- batch-1 network latency, recorded chains (Tables II-III quantity) ------
+        b.gspc_set_chain_fusion(1)
+        latency = {}
+        nets = [("wrn40x2_style", wl.wrn_chain, GROUPS, 2), ("resnet34_shaped", wl.resnet34_chain, (2, 4, 8, 16, 32), 3)]
+        for tag, make, gs, cfg in nets:
+            latency[tag] = {}
+            for g in gs:
+                ch = make(1, g)
+                weights = ch.make_weights(cfg)
+                packed = [b.gspc_pack_weights(torch.from_numpy(w).to(dev), gg) for w, gg in zip(weights, ch.weight_groups)]
+                bufs = [torch.empty(max(n, 1), dtype=torch.float32, device=dev) for n in ch.buf_elems]
+                bufs[0].copy_(torch.from_numpy(wl.make_input(ch.input_shape, 1)).reshape(-1))
+                lc = b.LayerChain(ch.layers, packed, bufs)
+                for _ in range(5):
+                    b.gspc_run_layer_chain(lc)
+                torch.cuda.synchronize()
+                reps = 50
+                ta = time.perf_counter()
+                for _ in range(reps):
+                    b.gspc_run_layer_chain(lc)
+                torch.cuda.synchronize()
+                latency[tag][str(g)] = round((time.perf_counter() - ta) / reps * 1e3, 4)
+                del lc, bufs, packed
 
     # ---- CPU oracle on a bounded sample -------------------------------------
     cpu = None
@@ -322,20 +388,64 @@ def main():
         import oracle
         cores = len(os.sched_getaffinity(0)) if hasattr(os, "sched_getaffinity") else os.cpu_count()
         cores = max(1, min(cores, oracle.max_threads(), 16))
-        n_s = 32
-        total, t_cpu = 0, 0.0
-        for g in GROUPS:
-            ch = wl.wrn_chain(n_s, g)
-            weights = ch.make_weights(2)
-            x0 = wl.make_input(ch.input_shape, wl.make_seed(2, 999, g))
-            ta = time.perf_counter()
-            oracle.run_chain(ch.layers, len(ch.buf_elems), x0, weights, threads=cores)
-            t_cpu += time.perf_counter() - ta
-            total += ch.macs()
+
+
+        def time_oracle(n_s, threads, runner):
+            total, t_cpu = 0, 0.0
+            for g in GROUPS:
+                ch = wl.wrn_chain(n_s, g)
+                weights = ch.make_weights(2)
+                x0 = wl.make_input(ch.input_shape, wl.make_seed(2, 999, g))
+                prep = runner(ch, weights, None, threads, prepare=True)
+                ta = time.perf_counter()
+                runner(ch, weights, x0, threads, prep=prep)
+                t_cpu += time.perf_counter() - ta
+                total += ch.macs()
+            return total, t_cpu
+
+        def run_definition(ch, weights, x0, threads, prepare=False, prep=None):
+            if prepare:
+                return None
+            oracle.run_chain(ch.layers, len(ch.buf_elems), x0, weights, threads=threads)
+
+        def tiles(l):
+            cpg, kpg = l.Cin // l.groups, l.Cout // l.groups
+            return (max(t for t in (1, 2, 3, 4) if cpg % t == 0), max(t for t in (1, 2, 4, 8, 16) if kpg % t == 0))
+
+        def run_alg1(ch, weights, x0, threads, prepare=False, prep=None):
+            # Algorithm 1 with the kernel reshape done ahead of time (Section III-B) and the
+            # convolution stage in its vectorised, multi-core schedule; a conv step's residual
+            # and ReLU as in oracle.run_chain
+            if prepare:
+                return [oracle.alg1_pack_kernels(weights[l.wid], l.groups, *tiles(l)) for l in ch.layers if l.op == "conv"]
+            bufs = [None] * len(ch.buf_elems)
+            bufs[0] = x0
+            k = 0
+            for l in ch.layers:
+                ti, to = tiles(l)
+                y = oracle.gspc_alg1(bufs[l.src], weights[l.wid], l.stride, l.pad, l.groups, ti, to, vectorised=True,
+                                     threads=threads, packed_w=prep[k])
+                k += 1
+                if l.src2 >= 0:
+                    y = oracle.add(y, bufs[l.src2])
+                bufs[l.dst] = oracle.relu(y) if l.relu else y
+
+        total, t_cpu = time_oracle(BATCH, cores, run_definition)
         cpu = {"value": round(total / t_cpu / 1e9, 3), "unit": "GMAC/s", "cores": cores,
                "kind": "oracle",
-               "sample": f"same WRN-40-2-style stacks, g in {list(GROUPS)}, batch {n_s} instead of "
-                         f"{BATCH} ({total / 1e9:.2f} GMAC, {t_cpu:.1f} s wall)"}
+               "sample": f"same WRN-40-2-style stacks, g in {list(GROUPS)}, batch {BATCH} "
+                         f"({total / 1e9:.2f} GMAC, {t_cpu:.1f} s wall)"}
+        total1, t1c = time_oracle(1, 1, run_definition)
+        cpu["single_thread"] = {"value": round(total1 / t1c / 1e9, 3), "unit": "GMAC/s", "cores": 1, "kind": "oracle",
+                                "sample": f"the same stacks at batch 1 ({total1 / 1e9:.2f} GMAC, {t1c:.1f} s wall)"}
+        totala, ta_ = time_oracle(BATCH, cores, run_alg1)
+        cpu["gspc_alg1_vectorised"] = {
+            "value": round(totala / ta_ / 1e9, 3), "unit": "GMAC/s", "cores": cores, "kind": "oracle (timed baseline only)",
+            "sample": f"the same stacks at batch {BATCH} through Algorithm 1: kernels packed ahead of time, input and output "
+                      f"reshapes timed, T_O <= 16 filters as one fp64 vector, (group, image) pairs over the cores "
+                      f"({totala / 1e9:.2f} GMAC, {ta_:.1f} s wall)"}
+        totalb, tb_ = time_oracle(1, 1, run_alg1)
+        cpu["gspc_alg1_vectorised"]["single_thread"] = round(totalb / tb_ / 1e9, 3)
 
     out = {
         "metric": "grouped conv2d GMAC/s (Eq. 2 MACs / time), WRN-40-2-style stack swept over g",
@@ -347,7 +457,10 @@ def main():
                    "batch": BATCH, "groups": list(GROUPS), "gmac_per_step": round(macs_step / 1e9, 3),
                    "streams": 1 if args.serial else len(GROUPS), "chain_fusion_in_step": bool(args.fusion)},
         "per_g": per_g,
+        "per_g_monotone": all(per_g[str(a)]["ms"] >= per_g[str(c)]["ms"] * 0.97 for a, c in zip(GROUPS, GROUPS[1:])),
         "roofline": roofline,
+        "roofline_hbm": roofline_hbm,
+        "latency_ms": latency,
         "cpu_baseline": cpu,
     }
     print(json.dumps(out))

@@ -47,6 +47,8 @@ def _load():
     lib.oracle_alg1_pack_inputs.argtypes = [_D] + [_I] * 7 + [_D]
     lib.oracle_alg1_conv.restype = _I
     lib.oracle_alg1_conv.argtypes = [_D, _D] + [_I] * 12 + [_D]
+    lib.oracle_alg1_conv_vec.restype = _I
+    lib.oracle_alg1_conv_vec.argtypes = [_D, _D] + [_I] * 12 + [_D, _I]
     lib.oracle_alg1_unpack_outputs.restype = _I
     lib.oracle_alg1_unpack_outputs.argtypes = [_D] + [_I] * 6 + [_D]
     lib.oracle_relu.restype = None
@@ -171,14 +173,21 @@ def alg1_pack_inputs(x, pad, groups, T_I):
 
 
 def alg1_conv(xp, wp, N, Cin, H, W, Cout, KH, KW, stride, pad, groups, T_I,
-              T_O):
-    """Algorithm 1 stage 3 -> Y' [g, N, KPG/T_O, Hout, Wout, T_O]."""
+              T_O, vectorised=False, threads=1):
+    """Algorithm 1 stage 3 -> Y' [g, N, KPG/T_O, Hout, Wout, T_O].  vectorised:
+    the CPU schedule of Sections III-B / III-C (T_O filters as one vector,
+    (group, image) pairs over `threads` cores), a timed baseline with the same
+    bits as the plain form."""
     xp, wp = _f64(xp), _f64(wp)
     KPG = Cout // groups
     Ho, Wo = out_dim(H, KH, stride, pad), out_dim(W, KW, stride, pad)
     yp = np.empty((groups, N, KPG // T_O, Ho, Wo, T_O), dtype=np.float64)
-    rc = _load().oracle_alg1_conv(_p(xp), _p(wp), N, Cin, H, W, Cout, KH, KW,
-                                  stride, pad, groups, T_I, T_O, _p(yp))
+    if vectorised:
+        rc = _load().oracle_alg1_conv_vec(_p(xp), _p(wp), N, Cin, H, W, Cout, KH, KW,
+                                          stride, pad, groups, T_I, T_O, _p(yp), threads)
+    else:
+        rc = _load().oracle_alg1_conv(_p(xp), _p(wp), N, Cin, H, W, Cout, KH, KW,
+                                      stride, pad, groups, T_I, T_O, _p(yp))
     _check(rc, "alg1_conv")
     return yp
 
@@ -194,15 +203,16 @@ def alg1_unpack_outputs(yp, Cout, groups, T_O):
     return y
 
 
-def gspc_alg1(x, w, stride, pad, groups, T_I, T_O):
-    """All four stages of Algorithm 1 in order."""
+def gspc_alg1(x, w, stride, pad, groups, T_I, T_O, vectorised=False, threads=1, packed_w=None):
+    """All four stages of Algorithm 1 in order (packed_w: a W' made ahead of time,
+    as the paper does for inference)."""
     x, w = _f64(x), _f64(w)
     N, Cin, H, W = x.shape
     Cout, _, KH, KW = w.shape
-    wp = alg1_pack_kernels(w, groups, T_I, T_O)
+    wp = packed_w if packed_w is not None else alg1_pack_kernels(w, groups, T_I, T_O)
     xp = alg1_pack_inputs(x, pad, groups, T_I)
     yp = alg1_conv(xp, wp, N, Cin, H, W, Cout, KH, KW, stride, pad, groups,
-                   T_I, T_O)
+                   T_I, T_O, vectorised=vectorised, threads=threads)
     return alg1_unpack_outputs(yp, Cout, groups, T_O)
 
 

@@ -17,8 +17,13 @@
  *   - oracle_macs           : the MAC formula of Section IV-B (Eq. 2).
  *   - oracle_conv2d_standard: Section II's standard convolution S, written
  *     with no notion of groups at all (used to pin the grouped routine).
- *   - oracle_alg1_*         : the four stages of Algorithm 1 taken literally
- *     (7-D W', 6-D X', 6-D Y', 4-D Y) with tile sizes T_O | KPG, T_I | CPG.
+ *   - oracle_alg1_*         : the four stages of Algorithm 1 (Section III-B)
+ *     restated with the printed listing's slips corrected (7-D W', 6-D X',
+ *     6-D Y', 4-D Y) for tile sizes T_O | KPG, T_I | CPG.
+ *   - oracle_alg1_conv_vec  : the convolution stage with the T_O filters of a
+ *     tile as one vector and (group, image) pairs over the cores, the CPU
+ *     schedule of Sections III-B / III-C; a timed baseline, pinned bit-identical
+ *     to oracle_alg1_conv.
  *   - relu / add / maxpool  : the non-convolution ops of the ResNet-style
  *     stacks of Section IV-A, needed to chain layers end to end.
  *
@@ -307,6 +312,61 @@ int oracle_alg1_conv(const double *xp, const double *wp, int N, int Cin, int H,
                                     }
                             yp[o++] = yv;
                         }
+    return 0;
+}
+
+/*
+ * Stage 3 as Section III-B / III-C schedule it on a CPU: the innermost T_O
+ * filters of a tile are one vector (they are contiguous in W' and in Y'), the
+ * input value is broadcast, and the (group, image) pairs are spread over the
+ * cores.  TIMED BASELINE ONLY ("the paper's method on the host"): nothing is
+ * checked against it.  Every output still sums its products in (c, kh, kw)
+ * order, one multiply and one add each, so the result is bit-identical to
+ * oracle_alg1_conv (pinned in the tests).  Same arguments as oracle_alg1_conv;
+ * threads > 1 splits the (group, image) loop nest over OpenMP threads.
+ */
+#define ALG1_MAX_TO 64
+#if defined(__x86_64__) && defined(__GNUC__) && !defined(__clang__)
+__attribute__((target_clones("avx512f", "avx2", "default")))
+#endif
+int oracle_alg1_conv_vec(const double *xp, const double *wp, int N, int Cin, int H,
+                         int W, int Cout, int KH, int KW, int stride, int pad,
+                         int groups, int T_I, int T_O, double *yp, int threads)
+{
+    if (!xp || !wp || !yp || groups <= 0 || Cin % groups || Cout % groups) return -1;
+    const int CPG = Cin / groups, KPG = Cout / groups;
+    if (T_I <= 0 || T_O <= 0 || T_O > ALG1_MAX_TO || CPG % T_I || KPG % T_O) return -1;
+    const int KT = KPG / T_O, CT = CPG / T_I;
+    const int Hp = H + 2 * pad, Wp = W + 2 * pad;
+    const int Hout = out_dim(H, KH, stride, pad);
+    const int Wout = out_dim(W, KW, stride, pad);
+    if (Hout <= 0 || Wout <= 0) return -1;
+    (void)threads;
+#ifdef _OPENMP
+#pragma omp parallel for collapse(2) num_threads(threads > 0 ? threads : 1)
+#endif
+    for (int j = 0; j < groups; ++j)
+        for (int n = 0; n < N; ++n)
+            for (int occ = 0; occ < KT; ++occ)
+                for (int oh = 0; oh < Hout; ++oh)
+                    for (int ow = 0; ow < Wout; ++ow) {
+                        double acc[ALG1_MAX_TO];
+                        for (int ocb = 0; ocb < T_O; ++ocb) acc[ocb] = 0.0;
+                        for (int c = 0; c < CPG; ++c)
+                            for (int kh = 0; kh < KH; ++kh)
+                                for (int kw = 0; kw < KW; ++kw) {
+                                    const double xv =
+                                        xp[(((((size_t)j * N + n) * CT + c / T_I) * Hp + (oh * stride + kh)) * T_I +
+                                            c % T_I) * Wp + (ow * stride + kw)];
+                                    const double *wv =
+                                        wp + ((((((size_t)j * KT + occ) * CT + c / T_I) * KH + kh) * KW + kw) * T_I +
+                                              c % T_I) * T_O;
+#pragma omp simd
+                                    for (int ocb = 0; ocb < T_O; ++ocb) acc[ocb] += xv * wv[ocb];
+                                }
+                        double *out = yp + (((((size_t)j * N + n) * KT + occ) * Hout + oh) * Wout + ow) * T_O;
+                        for (int ocb = 0; ocb < T_O; ++ocb) out[ocb] = acc[ocb];
+                    }
     return 0;
 }
 

@@ -243,6 +243,27 @@ def test_p9_algorithm1_equals_definition(N, Cin, Cout, H, W, g, K, stride, pad):
         assert np.array_equal(oracle.gspc_alg1(x, w, stride, pad, g, T_I, T_O), ref)
 
 
+@pytest.mark.parametrize("N,Cin,Cout,H,W,g,K,stride,pad,T_I,T_O", [
+    (2, 8, 16, 6, 5, 2, 3, 1, 1, 2, 8),
+    (3, 12, 12, 7, 7, 3, 3, 2, 1, 4, 4),
+    (2, 6, 6, 5, 5, 6, 3, 1, 1, 1, 1),       # depthwise
+    (1, 4, 32, 9, 8, 1, 1, 1, 0, 4, 16),
+    (1, 3, 24, 11, 11, 1, 7, 2, 3, 1, 3),    # a vector length that is not a power of two
+])
+def test_p9_vectorised_schedule_has_the_same_bits(N, Cin, Cout, H, W, g, K, stride, pad, T_I, T_O):
+    # The timed "paper's method on the host" baseline: T_O filters as one vector,
+    # (group, image) pairs over threads.  Same (c, kh, kw) order per output, so the
+    # same bits as the plain stage (and hence as the definition, by the test above).
+    x = _rand((N, Cin, H, W), 28)
+    w = _rand((Cout, Cin // g, K, K), 29)
+    ref = oracle.conv2d_grouped(x, w, stride, pad, g)
+    for threads in (1, 3):
+        got = oracle.gspc_alg1(x, w, stride, pad, g, T_I, T_O, vectorised=True, threads=threads)
+        assert np.array_equal(got, ref)
+    with pytest.raises(ValueError):
+        oracle.gspc_alg1(x, w, stride, pad, g, T_I, T_O + 1 if (Cout // g) % (T_O + 1) else 65, vectorised=True)
+
+
 def test_p9_depthwise_output_reshape_identity_for_batch_one():
     # Section III-B: for depthwise the output reshape is the identity (N = 1).
     yp = _rand((6, 1, 1, 4, 3, 1), 16)
