@@ -30,6 +30,7 @@ FAMILIES = {
     "b": ("conv_mfma16b<", range(6)),
     "q": ("conv_mfma4r<", (1, 2, 4)),
     "x": ("conv_wino<", range(7)),      # Winograd F(2x2, 3x3): fp32, 3x3, stride 1, pad 1
+    "r": ("conv_row16", range(9)),      # bf16 row products: 3x3, stride 1, pad 1, at most 16 channels per group
 }
 
 
@@ -50,15 +51,50 @@ def table_line(s, dtype, family, index):
             f"{1 if dtype == 'bf16' else 0} {family} {index}")
 
 
+SAMPLE = 2048   # output elements per layer that travel back to the parent for the agreement check
+
+
+def output_sample(b, torch, s, dtype, k):
+    """One launch of layer k on inputs that are the same in every child process; returns an
+    evenly spaced sample of the output and the output's RMS."""
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(1234 + k)
+    x = torch.rand((s.N, s.Cin, s.H, s.W), device="cuda", generator=gen) * 2 - 1
+    w = torch.randn((s.Cout, s.Cin // s.groups, s.KH, s.KW), device="cuda", generator=gen) * 0.1
+    pw = b.gspc_pack_weights(w, s.groups, b.GSPC_BF16 if dtype == "bf16" else b.GSPC_F32)
+    if dtype == "bf16":
+        x = b.gspc_pack_input_bf16(x)
+    y = b.gspc_conv2d_grouped(x, pw, s.N, s.Cin, s.H, s.W, s.Cout, s.KH, s.KW, s.stride, s.pad, s.groups).flatten()
+    torch.cuda.synchronize()
+    step = max(1, y.numel() // SAMPLE)
+    return y[::step][:SAMPLE].double().cpu().tolist(), float(y.double().pow(2).mean().sqrt())
+
+
 def probe(workload, batch, inner, reps):
-    """Child process: time every shape with whatever table the environment names."""
+    """Child process: time every shape with whatever table the environment names, and sample
+    every shape's output."""
     import torch
     from . import binding as b, layer_timing
     b.load()
     torch.cuda.set_stream(torch.cuda.Stream())
     shapes, dtype = workload_shapes(workload, batch)
     rows = layer_timing.time_layers(shapes, dtype, inner=inner, reps=reps)
-    print(json.dumps([{"kernel": r["kernel"], "us": r["us"]} for r in rows]))
+    b.gspc_set_stream()
+    out = []
+    for k, (s, r) in enumerate(zip(shapes, rows)):
+        sample, rms = output_sample(b, torch, s, dtype, k)
+        out.append({"kernel": r["kernel"], "us": r["us"], "sample": sample, "rms": rms})
+    print(json.dumps(out))
+
+
+def agrees(cand, base, tol=1e-5):
+    """A candidate's sampled output against the heuristic choice's (GPU against GPU, same inputs):
+    max difference relative to the output's RMS.  The kernels differ in summation order only,
+    which stays near 1e-6; a table must never select a configuration that computes something else."""
+    if len(cand["sample"]) != len(base["sample"]):
+        return False
+    den = max(base["rms"], 1e-30)
+    return max(abs(a - c) for a, c in zip(base["sample"], cand["sample"])) / den <= tol
 
 
 def run_child(args, table_path):
@@ -80,6 +116,9 @@ def main():
     ap.add_argument("--reps", type=int, default=5)
     ap.add_argument("--min-gain", type=float, default=0.03,
                     help="keep an entry only if it beats the heuristic choice by this fraction")
+    ap.add_argument("--tol", type=float, default=None,
+                    help="largest difference (relative to the output RMS) between a candidate's output and the heuristic "
+                         "choice's; default 1e-5 (fp32), 1e-4 (bf16, Winograd candidates)")
     ap.add_argument("--out", default=None, help="table file to write (default: stdout)")
     ap.add_argument("--probe", action="store_true", help=argparse.SUPPRESS)
     args = ap.parse_args()
@@ -90,9 +129,10 @@ def main():
     shapes, dtype = workload_shapes(args.workload, args.batch)
     base = run_child(args, None)
     best = [{"family": None, "index": None, "us": r["us"], "kernel": r["kernel"]} for r in base]
+    rejected = 0
     with tempfile.TemporaryDirectory() as tmp:
         # the bf16 kernel exists for bf16 inputs only, the resident-filter and Winograd kernels for fp32 only
-        for fam in (("b", "m", "q") if dtype == "bf16" else ("w", "m", "q", "x")):
+        for fam in (("b", "r", "m", "q") if dtype == "bf16" else ("w", "m", "q", "x")):
             prefix, indices = FAMILIES[fam]
             for idx in indices:
                 path = os.path.join(tmp, f"{fam}{idx}.tune")
@@ -103,6 +143,12 @@ def main():
                     # a candidate counts only where the planner took it: its family's kernel, and
                     # not the instance the heuristics pick anyway (that would be timing noise)
                     if r["kernel"].startswith(prefix) and r["kernel"] != base[k]["kernel"] and r["us"] < best[k]["us"]:
+                        tol = args.tol if args.tol is not None else (1e-4 if dtype == "bf16" or fam == "x" else 1e-5)
+                        if not agrees(r, base[k], tol):
+                            print(f"# rejected {fam}:{idx} for layer {k}: output differs from the heuristic choice's",
+                                  file=sys.stderr, flush=True)
+                            rejected += 1
+                            continue
                         best[k] = {"family": fam, "index": idx, "us": r["us"], "kernel": r["kernel"]}
                 print(f"# tried {fam}:{idx}", file=sys.stderr, flush=True)
     lines = [f"# libgspc tile table, workload {args.workload}, batch {args.batch}, dtype {dtype}",
@@ -116,7 +162,8 @@ def main():
             t1 += b1["us"]
         else:
             t1 += b0["us"]
-    lines.append(f"# sum over the layers: {t0:.1f} us with the heuristics, {t1:.1f} us with this table")
+    lines.append(f"# sum over the layers: {t0:.1f} us with the heuristics, {t1:.1f} us with this table; "
+                 f"{rejected} candidate measurements rejected because their output differed")
     text = "\n".join(lines) + "\n"
     if args.out:
         with open(args.out, "w") as f:

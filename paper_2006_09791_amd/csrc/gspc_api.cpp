@@ -137,6 +137,7 @@ int prepare_conv(const void *input, const gspc_packed_t *pw, int N, int Cin, int
     p->y = static_cast<float *>(output);
     p->res = nullptr;
     p->N = N; p->Cin = Cin; p->H = H; p->W = W; p->Cout = Cout; p->KH = KH; p->KW = KW;
+    p->H0 = H; p->W0 = W;
     p->stride = stride; p->pad = pad; p->groups = groups;
     p->CPG = Cin / groups; p->KPG = Cout / groups; p->Hout = Hout; p->Wout = Wout;
     p->KPGd = pw->geom.KPGd;

@@ -93,6 +93,7 @@ struct ConvParams {
     float *y;           // [N][Cout][Hout][Wout]
     const float *res;   // optional residual, same shape as y
     int N, Cin, H, W, Cout, KH, KW, stride, pad, groups;
+    int H0, W0;         // plane size as the caller gave it (H, W may be a re-pitched view of a 1x1 layer's planes)
     int CPG, KPG, Hout, Wout, KPGd;
     int relu;
     int in_bf16;

@@ -55,7 +55,8 @@ void load_table() {
 const Entry *find(const ConvParams &p) {
     std::call_once(g_once, load_table);
     if (g_table.empty()) return nullptr;
-    const Key k{p.N, p.Cin, p.H, p.W, p.Cout, p.KH, p.KW, p.stride, p.pad, p.groups, p.in_bf16 ? 1 : 0};
+    // keyed by the caller's plane size: 1x1 layers reach the planners with re-pitched planes
+    const Key k{p.N, p.Cin, p.H0, p.W0, p.Cout, p.KH, p.KW, p.stride, p.pad, p.groups, p.in_bf16 ? 1 : 0};
     auto it = g_table.find(k);
     return it == g_table.end() ? nullptr : &it->second;
 }

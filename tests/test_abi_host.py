@@ -182,3 +182,14 @@ def test_minimal_filtering_identity_used_by_the_winograd_kernel():
             direct[i, j] = np.sum(d[:, i:i + 3, j:j + 3] * g)
     M = sum((G @ g[c] @ G.T) * (BT @ d[c] @ BT.T) for c in range(C))
     assert np.allclose(AT @ M @ AT.T, direct, rtol=1e-12, atol=1e-12)
+
+
+def test_autotuner_rejects_a_candidate_whose_output_differs():
+    """The offline tuner accepts a (family, tile) only if its sampled output agrees with the
+    heuristic choice's: the rule itself, on made-up samples."""
+    from paper_2006_09791_amd import autotune
+    base = {"sample": [1.0, 2.0, -3.0], "rms": 2.0}
+    assert autotune.agrees({"sample": [1.0, 2.0, -3.00001], "rms": 2.0}, base)
+    assert not autotune.agrees({"sample": [1.0, 2.0, -3.001], "rms": 2.0}, base)
+    assert autotune.agrees({"sample": [1.0, 2.0, -3.001], "rms": 2.0}, base, tol=1e-3)
+    assert not autotune.agrees({"sample": [1.0, 2.0], "rms": 2.0}, base)

@@ -352,6 +352,37 @@ def test_tile_table_overrides_the_planner(gpu, tmp_path):
     assert lines[2].startswith("conv_wino<1,1,2,2,") and lines[2].endswith("True"), out
 
 
+def test_tile_table_is_keyed_by_the_callers_plane_size(gpu, tmp_path):
+    """A 1x1 layer on 14x14 planes reaches the planners as a re-pitched plane; its table line,
+    written with the caller's H and W, must still be found."""
+    import subprocess, sys, os, textwrap
+    table = tmp_path / "t.tune"
+    table.write_text("64 64 14 14 128 1 1 1 0 1 0 m 8\n")
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    code = textwrap.dedent(f"""
+        import sys
+        sys.path.insert(0, {root!r}); sys.path.insert(0, {os.path.join(root, "tests")!r})
+        import torch, oracle
+        from paper_2006_09791_amd import binding as b, workloads as wl
+        from helpers import rel_err
+        s = wl.ConvShape(64, 64, 14, 14, 128, 1, 1, 1, 0, 1)
+        x = wl.make_input((s.N, s.Cin, s.H, s.W), 3); w = wl.make_weight(s.Cout, s.Cin, 1, 1, 4)
+        pw = b.gspc_pack_weights(torch.from_numpy(w).cuda(), 1)
+        y = torch.empty((s.N, s.Cout, s.H, s.W), device="cuda")
+        b.gspc_conv2d_grouped(torch.from_numpy(x).cuda(), pw, s.N, s.Cin, s.H, s.W, s.Cout, 1, 1, 1, 0, 1, y)
+        torch.cuda.synchronize()
+        print(b.gspc_last_kernel(), rel_err(y.cpu().numpy(), oracle.conv2d_grouped(x, w, 1, 0, 1, threads=8)) < 1e-4)
+    """)
+    names = []
+    for env in (dict(os.environ, GSPC_TUNE_FILE=str(table)), {k: v for k, v in os.environ.items() if k != "GSPC_TUNE_FILE"}):
+        out = subprocess.run([sys.executable, "-c", code], env=env, check=True, capture_output=True, text=True).stdout
+        line = [l for l in out.strip().splitlines() if l.startswith("conv_")][-1]
+        assert line.endswith("True"), out
+        names.append(line.split()[0])
+    assert names[0].startswith("conv_mfma16<1,1,1,4,1,1,1,f32,"), names      # configuration 8 of family 'm'
+    assert names[0] != names[1], names                                       # the heuristic choice is another one
+
+
 # Filters per group that are not a multiple of 16 (the G(g) forms of a MobileNetV2-shaped
 # network, Section IV-A: 96, 144, 192, 384, 576 and 960 channels over 2..16 groups): the plain
 # 16x16x4 kernel zero-pads the last filter tile and drops its padding filters at the store.
