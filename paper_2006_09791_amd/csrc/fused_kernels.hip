@@ -242,6 +242,22 @@ hipError_t launch_core(const FusedRun &r, size_t lds, hipStream_t s) {
     return hipGetLastError();
 }
 
+// The layer as the fused kernel multiplies it: its widest merged direct section if it has one
+// (block-diagonal groups of up to 8 channels fill more of each matrix-core instruction), else its own
+// direct section.
+struct FuseView {
+    int groups, CPG, KPGd;
+    const float *w;
+};
+FuseView fuse_view(const gspc_layer_t &L) {
+    const PackGeom &g = L.w->geom;
+    for (int which = 1; which >= 0; --which)
+        if (g.md[which].m && g.md[which].groups >= 2)
+            return FuseView{g.md[which].groups, g.md[which].CPG, g.md[which].KPGd,
+                            reinterpret_cast<const float *>(static_cast<const char *>(L.w->dev) + g.md[which].offset)};
+    return FuseView{L.groups, L.Cin / L.groups, g.KPGd, reinterpret_cast<const float *>(L.w->dev)};
+}
+
 bool fusable_layer(const gspc_layer_t &L) {
     if (L.op != GSPC_OP_CONV || !L.w) return false;
     if (L.KH != 3 || L.KW != 3 || L.stride != 1 || L.pad != 1 || L.Cin != L.Cout) return false;
@@ -273,9 +289,10 @@ int plan_fused_run(const gspc_layer_t *layers, int first, int count, void *const
     r.C = A.Cin;
     r.H = A.H;
     r.W = A.W;
-    r.groups = A.groups;
-    r.CPG = A.Cin / A.groups;
-    r.KPGd = A.w->geom.KPGd;
+    const FuseView av = fuse_view(A);
+    r.groups = av.groups;
+    r.CPG = av.CPG;
+    r.KPGd = av.KPGd;
     r.vec = A.W % 4 == 0;
     r.XO = 4;
     r.LW = round_up(r.XO + r.W + 1, 4);
@@ -336,7 +353,7 @@ int plan_fused_run(const gspc_layer_t *layers, int first, int count, void *const
         for (int l = 0; l < n && ok; ++l) {
             const gspc_layer_t &L = layers[first + l];
             FusedLayer &F = r.L[l];
-            F.w = reinterpret_cast<const float *>(L.w->dev);
+            F.w = fuse_view(L).w;
             F.src = (short)vals[src_v[l]].tile;
             F.res = (short)(res_v[l] >= 0 ? vals[res_v[l]].tile : -1);
             F.relu = (L.flags & GSPC_FLAG_RELU) ? 1 : 0;

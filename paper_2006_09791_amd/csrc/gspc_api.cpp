@@ -177,6 +177,32 @@ int prepare_conv(const void *input, const gspc_packed_t *pw, int N, int Cin, int
 
 // Picks the kernel family and launches.
 int dispatch_conv(const gspc::ConvParams &p, const gspc_packed_t *pw) {
+    // Groups too small for a matrix-core tile: the layer as block-diagonal groups of at least four
+    // channels and filters (zero weights between the original groups, Section II / Fig. 2), which the
+    // 4x4x1 kernel takes; a layer with 2 channels per group then runs exactly as the one with half
+    // as many groups does.
+    if (pw->geom.md[0].m && t_force_path != GSPC_PATH_DIRECT && !p.in_bf16) {
+        const gspc::PackGeom::MergedDirect &d = pw->geom.md[0];
+        gspc::ConvParams q = p;
+        q.groups = d.groups;
+        q.CPG = d.CPG;
+        q.KPG = d.KPG;
+        q.KPGd = d.KPGd;
+        q.wd = reinterpret_cast<const float *>(static_cast<const char *>(pw->dev) + d.offset);
+        q.wm = nullptr;
+        q.wb = nullptr;
+        q.wx = nullptr;
+        q.wr = nullptr;
+        const gspc::PackGeom gm = gspc::merged_geom(pw->geom, 0, p.KH, p.KW);
+        if (gspc::mfma_supported(q, gm)) {
+            const char *name = "";
+            const hipError_t e = gspc::launch_mfma(q, gm, t_stream, &name);
+            if (e != hipSuccess) return hip_fail(e, "convolution launch");
+            t_last_path = GSPC_PATH_MFMA;
+            t_last_kernel = name;
+            return GSPC_OK;
+        }
+    }
     const bool can_mfma = gspc::mfma_supported(p, pw->geom);
     int path = t_force_path;
     if (path == GSPC_PATH_AUTO) path = can_mfma ? GSPC_PATH_MFMA : GSPC_PATH_DIRECT;
@@ -265,7 +291,38 @@ PackGeom make_pack_geom(int Cin, int Cout, int KH, int KW, int groups, int dtype
         g.wino_bytes = (size_t)groups * (g.CPG / 4) * ((g.KPG + 15) / 16) * 4096;
         g.total_bytes = g.wino_offset + g.wino_bytes;
     }
+    if (KH == 3 && KW == 3 && g.CPG * g.KPG > 1) {
+        const int lo = g.CPG < g.KPG ? g.CPG : g.KPG;
+        for (int which = 0; which < 2; ++which) {
+            const int target = which == 0 ? 4 : 8;
+            int m = 1;
+            while (lo * m < target && m < 8 && groups % (2 * m) == 0) m *= 2;
+            if (m == 1 || lo * m < target || g.CPG * m > 32 || g.KPG * m > 32) continue;
+            if (which == 1 && g.md[0].m == m) continue;   // the same view
+            PackGeom::MergedDirect &d = g.md[which];
+            d.m = m;
+            d.groups = groups / m;
+            d.CPG = g.CPG * m;
+            d.KPG = g.KPG * m;
+            d.KPGd = round_up(d.KPG, 4);
+            d.offset = (g.total_bytes + 255) / 256 * 256;
+            d.bytes = (size_t)d.groups * d.CPG * 9 * d.KPGd * sizeof(float);
+            g.total_bytes = d.offset + d.bytes;
+        }
+    }
     return g;
+}
+
+PackGeom merged_geom(const PackGeom &g, int which, int KH, int KW) {
+    const PackGeom::MergedDirect &d = g.md[which];
+    PackGeom v{};
+    v.CPG = d.CPG;
+    v.KPG = d.KPG;
+    v.Kred = d.CPG * KH * KW;
+    v.KPGd = d.KPGd;
+    v.variant = d.KPG % 16 == 0 ? kMfma16 : d.KPG % 4 == 0 ? kMfma4 : kMfmaNone;
+    v.direct_bytes = d.bytes;
+    return v;
 }
 
 }  // namespace gspc

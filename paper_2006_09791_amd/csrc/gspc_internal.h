@@ -65,7 +65,18 @@ struct PackGeom {
     // filter l % 16 of its tile at channel 4*cblk + l / 16, and its four values in
     // quad q are the transformed-domain positions 4*q .. 4*q + 3 (position = 4*xi + nu).
     size_t wino_bytes, wino_offset;
+    // Merged direct sections (3x3, fewer than 4 or 8 channels or filters per group, not depthwise):
+    // the layer seen as groups / m block-diagonal groups of m * CPG channels and m * KPG filters, in
+    // the direct section's layout [groups/m][m*CPG*9][round_up(m*KPG, 4)].  md[0] reaches at least 4
+    // channels and filters per group (the smallest the 4x4x1 matrix-core kernel takes), md[1] at
+    // least 8 (what the depth-fused runs multiply best); m = 0: none.
+    struct MergedDirect {
+        int m, groups, CPG, KPG, KPGd;
+        size_t bytes, offset;
+    } md[2];
 };
+// Geometry of the layer as merged section `which` sees it (sections other than direct: none).
+PackGeom merged_geom(const PackGeom &g, int which, int KH, int KW);
 
 PackGeom make_pack_geom(int Cin, int Cout, int KH, int KW, int groups, int dtype);
 

@@ -104,6 +104,22 @@ __device__ __forceinline__ float merged_weight(const float *__restrict__ w, cons
     return w[(size_t)oc * a.Kred + (size_t)(cm % a.CPG) * 9 + tap];
 }
 
+// Merged direct section [groups/m][m*CPG*9][KPGd2] (3x3 layers): the direct section of the layer
+// seen as groups / m block-diagonal groups.
+__global__ void pack_direct_merged_kernel(const float *__restrict__ w, float *__restrict__ out, PackArgs a, int m,
+                                          int KPGd2, size_t total) {
+    size_t d = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (d >= total) return;
+    const int o = (int)(d % KPGd2);
+    const size_t r = d / KPGd2;
+    const int kred2 = a.CPG * m * 9;
+    const int k = (int)(r % kred2);
+    const int j = (int)(r / kred2);
+    float v = merged_weight(w, a, m, j, o, k / 9, k % 9);
+    if (a.to_bf16) v = round_bf16(v);
+    out[d] = v;
+}
+
 // bf16 matrix-core section, one thread per 2-byte element; m = groups merged per section group.
 __global__ void pack_bf16_kernel(const float *__restrict__ w, uint16_t *__restrict__ out, PackArgs a,
                                  int ckb, int ks_b, int nchunks, int m, size_t total) {
@@ -225,6 +241,16 @@ hipError_t launch_pack_weights(const float *w, const gspc_packed *h, hipStream_t
         float *xsec = reinterpret_cast<float *>(static_cast<char *>(h->dev) + h->geom.wino_offset);
         const size_t nx = h->geom.wino_bytes / sizeof(float);
         hipLaunchKernelGGL(pack_wino_kernel, dim3(blocks_for(nx, 256)), dim3(256), 0, s, w, xsec, a, nx);
+        e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    for (int which = 0; which < 2; ++which) {
+        const PackGeom::MergedDirect &md = h->geom.md[which];
+        if (!md.m) continue;
+        float *dsec2 = reinterpret_cast<float *>(static_cast<char *>(h->dev) + md.offset);
+        const size_t n2 = md.bytes / sizeof(float);
+        hipLaunchKernelGGL(pack_direct_merged_kernel, dim3(blocks_for(n2, 256)), dim3(256), 0, s, w, dsec2, a, md.m,
+                           md.KPGd, n2);
         e = hipGetLastError();
         if (e != hipSuccess) return e;
     }

@@ -297,6 +297,20 @@ def test_bf16_row_kernel_with_residual_and_relu(gpu):
         assert rel_err(got, ref[l.dst]) < 1e-4, li
 
 
+@pytest.mark.parametrize("s,expect", [
+    (S(5, 32, 12, 12, 32, 3, 3, 1, 1, 16), "conv_mfma4r<4,"),    # 2 and 2 -> pairs of groups as 4 and 4
+    (S(3, 16, 9, 8, 32, 3, 3, 2, 1, 8), "conv_mfma4r<4,"),       # 2 channels, 4 filters -> 4 and 8, stride 2
+    (S(2, 8, 10, 10, 16, 3, 3, 1, 1, 8), "conv_mfma4r<4,"),      # 1 channel, 2 filters (channel multiplier) -> 4 and 8
+    (S(2, 12, 7, 7, 12, 3, 3, 1, 1, 6), None),                   # six groups of 2: pairs merge, three merged groups
+])
+def test_small_groups_run_as_merged_groups(gpu, s, expect):
+    """Groups of fewer than four channels or filters run as block-diagonal merged groups on the
+    4x4x1 matrix-core kernel (fp32): same result as the definition, which never mixes groups."""
+    name = check(gpu, s, seed=37)
+    if expect:
+        assert name.startswith(expect), name
+
+
 def test_rerun_is_bit_identical(gpu):
     s = wl.wrn_grouped_shapes(2, 2)[2]
     y1, *_ = run_conv(gpu, s, seed=31)
