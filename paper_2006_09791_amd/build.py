@@ -12,7 +12,7 @@ LIB = os.path.join(HERE, "libgspc.so")
 
 SOURCES = ["gspc_api.cpp", "pack_kernels.hip", "chain_kernels.hip",
            "direct_kernels.hip", "mfma_kernels.hip", "mfma4_kernels.hip", "mfmab_kernels.hip",
-           "mfmaw_kernels.hip", "fused_kernels.hip", "dw_kernels.hip", "dwpw_kernels.hip", "wino_kernels.hip", "rowb_kernels.hip", "tune_table.cpp"]
+           "mfmaw_kernels.hip", "fused_kernels.hip", "dw_kernels.hip", "dwpw_kernels.hip", "wino_kernels.hip", "rowb_kernels.hip", "gpw_kernels.hip", "tune_table.cpp"]
 
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-x", "hip",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

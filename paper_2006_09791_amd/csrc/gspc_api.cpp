@@ -286,10 +286,24 @@ PackGeom make_pack_geom(int Cin, int Cout, int KH, int KW, int groups, int dtype
             g.total_bytes = g.row_offset + g.row_bytes;
         }
     }
-    if (dtype == GSPC_F32 && KH == 3 && KW == 3 && g.KPG >= 12 && g.CPG % 4 == 0 && g.CPG >= 8) {
-        g.wino_offset = (g.total_bytes + 255) / 256 * 256;
-        g.wino_bytes = (size_t)groups * (g.CPG / 4) * ((g.KPG + 15) / 16) * 4096;
-        g.total_bytes = g.wino_offset + g.wino_bytes;
+    if (dtype == GSPC_F32 && (Cin == 32 || Cin == 64 || Cin == 128)) {
+        int m = 0;
+        if (KH == 3 && KW == 3 && Cin == Cout && groups < Cin) {
+            m = 1;
+            while ((g.KPG * m) % 16 && groups % (2 * m) == 0) m *= 2;
+            if ((g.KPG * m) % 16) m = 0;
+        } else if (KH == 1 && KW == 1 && groups == 1 && Cout % 16 == 0) {
+            m = 1;
+        }
+        if (m) {
+            g.qk_m = m;
+            g.qk_groups = groups / m;
+            g.qk_CPG = g.CPG * m;
+            g.qk_KPG = g.KPG * m;
+            g.qk_offset = (g.total_bytes + 255) / 256 * 256;
+            g.qk_bytes = (size_t)g.qk_groups * (g.qk_CPG / 4 * KH * KW / 4) * (g.qk_KPG / 16) * 1024;
+            g.total_bytes = g.qk_offset + g.qk_bytes;
+        }
     }
     if (KH == 3 && KW == 3 && g.CPG * g.KPG > 1) {
         const int lo = g.CPG < g.KPG ? g.CPG : g.KPG;
@@ -309,6 +323,12 @@ PackGeom make_pack_geom(int Cin, int Cout, int KH, int KW, int groups, int dtype
             d.bytes = (size_t)d.groups * d.CPG * 9 * d.KPGd * sizeof(float);
             g.total_bytes = d.offset + d.bytes;
         }
+    }
+    // (the Winograd section stays the last one)
+    if (dtype == GSPC_F32 && KH == 3 && KW == 3 && g.KPG >= 12 && g.CPG % 4 == 0 && g.CPG >= 8) {
+        g.wino_offset = (g.total_bytes + 255) / 256 * 256;
+        g.wino_bytes = (size_t)groups * (g.CPG / 4) * ((g.KPG + 15) / 16) * 4096;
+        g.total_bytes = g.wino_offset + g.wino_bytes;
     }
     return g;
 }
@@ -579,29 +599,38 @@ int gspc_run_layer_chain(const gspc_layer_t *layers, int n_layers, void *const *
             int first, count;
             gspc::FusedPlan *plan;
             gspc::DwPwPlan *pair;
+            gspc::GpwPlan *gpair;
         };
         std::vector<Step> steps;
         std::vector<std::unique_ptr<gspc::FusedPlan>> plans;
         std::vector<std::unique_ptr<gspc::DwPwPlan>> pairs;
+        std::vector<std::unique_ptr<gspc::GpwPlan>> gpairs;
         for (int i = 0; i < n_layers;) {
             int covered = 0;
             if (t_fusion && t_force_path == GSPC_PATH_AUTO) {
                 auto pl = std::make_unique<gspc::FusedPlan>();
                 covered = gspc::plan_fused_run(layers, i, n_layers - i, act_bufs, pl.get());
                 if (covered > 0) {
-                    steps.push_back({i, covered, pl.get(), nullptr});
+                    steps.push_back({i, covered, pl.get(), nullptr, nullptr});
                     plans.push_back(std::move(pl));
                 } else {
                     auto pr = std::make_unique<gspc::DwPwPlan>();
                     covered = gspc::plan_dwpw(layers, i, n_layers - i, act_bufs, pr.get());
                     if (covered > 0) {
-                        steps.push_back({i, covered, nullptr, pr.get()});
+                        steps.push_back({i, covered, nullptr, pr.get(), nullptr});
                         pairs.push_back(std::move(pr));
+                    } else {
+                        auto gp = std::make_unique<gspc::GpwPlan>();
+                        covered = gspc::plan_gpw(layers, i, n_layers - i, act_bufs, gp.get());
+                        if (covered > 0) {
+                            steps.push_back({i, covered, nullptr, nullptr, gp.get()});
+                            gpairs.push_back(std::move(gp));
+                        }
                     }
                 }
             }
             if (covered == 0) {
-                steps.push_back({i, 1, nullptr, nullptr});
+                steps.push_back({i, 1, nullptr, nullptr, nullptr});
                 covered = 1;
             }
             i += covered;
@@ -616,6 +645,10 @@ int gspc_run_layer_chain(const gspc_layer_t *layers, int n_layers, void *const *
                     const hipError_t e = gspc::launch_dwpw(*st.pair, t_stream, &t_last_kernel);
                     if (e != hipSuccess) return hip_fail(e, "fused pair launch");
                     t_last_path = GSPC_PATH_MFMA;
+                } else if (st.gpair) {
+                    const hipError_t e = gspc::launch_gpw(*st.gpair, t_stream, &t_last_kernel);
+                    if (e != hipSuccess) return hip_fail(e, "fused pair launch");
+                    t_last_path = GSPC_PATH_MFMA;
                 } else {
                     const int rc2 = launch_step(st.first);
                     if (rc2 != GSPC_OK) return rc2;
@@ -628,7 +661,7 @@ int gspc_run_layer_chain(const gspc_layer_t *layers, int n_layers, void *const *
                                hipStreamIsCapturing(t_stream, &cap) == hipSuccess &&
                                cap == hipStreamCaptureStatusNone;
         if (try_graph) {
-            const uint64_t key = chain_key(layers, n_layers, act_bufs, n_bufs, t_stream, t_force_path, t_fusion + 2 * (gspc::winograd_mode() + 1));
+            const uint64_t key = chain_key(layers, n_layers, act_bufs, n_bufs, t_stream, t_force_path, t_fusion + 2 * (gspc::winograd_mode() + 1) + 8 * (gspc::gpw_enabled() ? 1 : 0));
             auto it = t_graphs.find(key);
             if (it == t_graphs.end()) {
                 hipGraph_t graph = nullptr;

@@ -70,6 +70,14 @@ struct PackGeom {
     // the direct section's layout [groups/m][m*CPG*9][round_up(m*KPG, 4)].  md[0] reaches at least 4
     // channels and filters per group (the smallest the 4x4x1 matrix-core kernel takes), md[1] at
     // least 8 (what the depth-fused runs multiply best); m = 0: none.
+    // Quad-k section (GSPC_F32 handles; conv_gpw's operands): fp32 [qk_groups][k-steps / 4][qk_KPG / 16]
+    // [64 lanes][4]: lane l, element e holds the weight of filter 16*tile + l % 16 at k-step 4*quad + e,
+    // k-steps ordered (c / 4, kh, kw) with channel 4 * (k-step / taps) + l / 16.  For 3x3 layers with
+    // Cin = Cout in {32, 64, 128}: qk_m original groups merged until a group has a multiple of 16
+    // filters (block-diagonal); for ungrouped 1x1 layers with Cin in {32, 64, 128} and Cout % 16 == 0:
+    // the layer itself.
+    int qk_m, qk_groups, qk_CPG, qk_KPG;
+    size_t qk_bytes, qk_offset;
     struct MergedDirect {
         int m, groups, CPG, KPG, KPGd;
         size_t bytes, offset;
@@ -210,6 +218,17 @@ struct DwPwPlan {
 // 2 if layers[first], layers[first + 1] run as one fused launch, else 0.
 int plan_dwpw(const gspc_layer_t *layers, int first, int count, void *const *bufs, DwPwPlan *out);
 hipError_t launch_dwpw(const DwPwPlan &plan, hipStream_t s, const char **name);
+
+// Grouped 3x3 + pointwise 1x1 pair as one kernel (gpw_kernels.hip); plan is opaque to the caller.
+struct GpwPlan {
+    int ct, mta, kt, stride;
+    alignas(8) char params[96];
+    alignas(8) char tile[128];
+};
+// 2 if layers[first], layers[first + 1] run as one fused launch, else 0.
+int plan_gpw(const gspc_layer_t *layers, int first, int count, void *const *bufs, GpwPlan *out);
+hipError_t launch_gpw(const GpwPlan &plan, hipStream_t s, const char **name);
+bool gpw_enabled();   // GSPC_GPW=1 in the environment, read at every call
 
 hipError_t launch_pack_weights(const float *w, const gspc_packed *h, hipStream_t s);
 hipError_t launch_unpack_weights(const gspc_packed *h, int which, float *w, hipStream_t s);

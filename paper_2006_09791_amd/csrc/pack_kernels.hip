@@ -120,6 +120,27 @@ __global__ void pack_direct_merged_kernel(const float *__restrict__ w, float *__
     out[d] = v;
 }
 
+// Quad-k section [groups/m][k-steps/4][m*KPG/16][64 lanes][4], taps = KH*KW (9 or 1).
+__global__ void pack_quadk_kernel(const float *__restrict__ w, float *__restrict__ out, PackArgs a, int m, size_t total) {
+    size_t d = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (d >= total) return;
+    const int taps = a.KH * a.KW;
+    const int e = (int)(d % 4);
+    size_t r = d / 4;
+    const int lane = (int)(r % 64);
+    r /= 64;
+    const int mtiles = a.KPG * m / 16, quads = a.CPG * m / 4 * taps / 4;
+    const int mt = (int)(r % mtiles);
+    r /= mtiles;
+    const int quad = (int)(r % quads);
+    const int j = (int)(r / quads);
+    const int ks = 4 * quad + e, cm = (ks / taps) * 4 + lane / 16, tap = ks % taps, fo = mt * 16 + lane % 16;
+    float v = 0.f;
+    if (fo / a.KPG == cm / a.CPG)   // same original group
+        v = w[(size_t)(j * a.KPG * m + fo) * a.Kred + (size_t)(cm % a.CPG) * taps + tap];
+    out[d] = v;
+}
+
 // bf16 matrix-core section, one thread per 2-byte element; m = groups merged per section group.
 __global__ void pack_bf16_kernel(const float *__restrict__ w, uint16_t *__restrict__ out, PackArgs a,
                                  int ckb, int ks_b, int nchunks, int m, size_t total) {
@@ -241,6 +262,13 @@ hipError_t launch_pack_weights(const float *w, const gspc_packed *h, hipStream_t
         float *xsec = reinterpret_cast<float *>(static_cast<char *>(h->dev) + h->geom.wino_offset);
         const size_t nx = h->geom.wino_bytes / sizeof(float);
         hipLaunchKernelGGL(pack_wino_kernel, dim3(blocks_for(nx, 256)), dim3(256), 0, s, w, xsec, a, nx);
+        e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    if (h->geom.qk_bytes) {
+        float *qsec = reinterpret_cast<float *>(static_cast<char *>(h->dev) + h->geom.qk_offset);
+        const size_t nq = h->geom.qk_bytes / sizeof(float);
+        hipLaunchKernelGGL(pack_quadk_kernel, dim3(blocks_for(nq, 256)), dim3(256), 0, s, w, qsec, a, h->geom.qk_m, nq);
         e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
