@@ -25,7 +25,8 @@
 
 namespace gspc {
 
-constexpr int kTmaxW = 4;    // input staging slots (16 bytes per lane each) per chunk
+constexpr int kTmaxW = 4;    // input staging slots (16 bytes per lane each) per chunk (stride 1)
+constexpr int kTmaxW2 = 8;   // the same for stride 2, whose tiles span twice the input rows at twice the width
 constexpr int kWmaxW = 20;   // weight staging slots (16 bytes per thread each), whole reduction
 
 struct Tile16w {
@@ -57,7 +58,7 @@ template <int MI, int NI, int S, int CKB, bool PERSIST, typename TIN>
 __global__ __launch_bounds__(256) void conv_mfma16w(ConvParams p, Tile16w t) {
     GSPC_STAMPW(0)
     constexpr int NT = 256, TAPS = 9, CK = 4 * CKB, KCHUNK = CKB * TAPS, ES = (int)sizeof(TIN);
-    constexpr int TMAX = kTmaxW, WMAX = kWmaxW;
+    constexpr int TMAX = S == 2 ? kTmaxW2 : kTmaxW, WMAX = kWmaxW;
     constexpr int W0 = (KCHUNK * MI * 16 + NT - 1) / NT;   // weight slots the first chunk needs
     extern __shared__ f32x4 smem4[];
     float *smem = reinterpret_cast<float *>(smem4);
@@ -460,7 +461,7 @@ bool planW_cfg(const ConvParams &p, const PackGeom &g, const CfgW &c, int ckb, T
     const int rpp = 64 >> t.tpr_log2;
     t.tasks = CK * t.NB * t.IHt;
     t.xslots = (t.tasks + rpp - 1) / rpp;
-    if (t.xslots > kTmaxW) return false;
+    if (t.xslots > (p.stride == 2 ? kTmaxW2 : kTmaxW)) return false;
     t.ksteps = g.ksteps;
     t.mtiles = g.mtiles;
     t.nchunks = g.CPG / CK;
@@ -550,12 +551,13 @@ bool plan_mfma16w(const ConvParams &p, const PackGeom &g, Mfma16wPlan *out) {
     if (off || g.variant != kMfma16 || !p.wm || p.in_bf16 || p.KH != 3 || p.KW != 3 ||
         (p.stride != 1 && p.stride != 2) || p.W % 4 || g.CPG % 4 || g.CPGp != g.CPG)
         return false;
-    // Findings of the tile-table autotuner for stride-2 layers, for which this kernel has only
-    // its smallest tile: the plain 16x16x4 kernel is 6-20 % faster with at most 8 channels per
-    // group, 10-20 % faster at batch 256 and 10-25 % faster at batch 16 and below; in between
-    // (batch 64, more channels per group) this one wins by up to 30 %.  A table can overrule.
+    // Findings of the tile-table autotuner for stride-2 layers: the plain 16x16x4 kernel is 6-20 %
+    // faster with at most 8 channels per group and 10-25 % faster at batch 16 and below; at batch 64
+    // this kernel wins by up to 30 %; at batch 128 and above it wins (7-17 %, with the larger
+    // stride-2 tiles that eight staging slots allow) from 32 channels per group on and loses
+    // below.  A table can overrule.
     const bool asked = tuned_family(p) == 'w';
-    if (p.stride == 2 && !asked && (g.CPG <= 8 || p.N >= 128 || p.N <= 16)) return false;
+    if (p.stride == 2 && !asked && (g.CPG <= 8 || (p.N >= 128 && g.CPG < 32) || p.N <= 16)) return false;
     static const char *force = std::getenv("GSPC_TILEW");
     const int ckb = g.CPG % 8 == 0 ? 2 : 1;
     int forced = force ? std::atoi(force) : tuned_config(p, 'w');
