@@ -13,6 +13,11 @@
 // For the plane widths of the MobileNet / ResNet tails (WT = 28, 14, 7) a thread produces a whole
 // output row: three tile rows pass through registers once, no index arithmetic per output, and
 // the row leaves as 16-, 8- or 4-byte stores; other widths take one output per thread and step.
+//
+// Launches that fill the chip on 56x56, 28x28, 14x14 and 7x7 planes take conv_dw_wave instead
+// (further down): whole planes per wavefront, no block-level barrier, every global and almost
+// every LDS access 16 bytes wide.  The block form above keeps the small launches (it shrinks its
+// tiles to spread over the chip) and the other plane sizes.
 #include <cstdlib>
 #include <cstring>
 
@@ -171,11 +176,270 @@ __global__ __launch_bounds__(256) void conv_direct_dw(ConvParams p, TileD t) {
     }
 }
 
+
+// ---- whole planes per wavefront -------------------------------------------------------------
+// For the square planes of the network tails (28x28, 14x14, 7x7) a wavefront takes G consecutive
+// planes by itself: their floats are one contiguous, 16-byte aligned piece of the input and their
+// outputs one contiguous piece of the output.  The piece is copied flat into a wave-private LDS
+// region (16-byte loads and LDS writes, no re-pitch and no halo: the left and right padding
+// columns are dropped from the unrolled sums at compile time, the top and bottom padding rows are
+// selected to zero per lane), a lane reads the (R-1)*S + 3 input rows of its R output rows as one
+// contiguous window into registers, multiplies them out, writes the R*Wout results back into the
+// region at their flat output position (the region is reused: every lane has its window in
+// registers by then), and the wave reads the results back 16 bytes per lane in flat order for
+// coalesced stores (residual and ReLU applied there).  LDS operations of one wavefront execute in
+// order, so no barrier is needed anywhere; memory clobbers keep the compiler from reordering the
+// phases.  Per lane and R*Wout outputs this takes a few dozen wide LDS operations where the
+// per-output form above takes nine 4-byte reads per output.
+template <int S, int H, int W, int R, int CP = -1>
+struct DwWaveGeom {
+    static constexpr int Hout = (H - 1) / S + 1, Wout = (W - 1) / S + 1;
+    static constexpr int HW = H * W, HoWo = Hout * Wout;
+    static constexpr int LP = (Hout + R - 1) / R;           // lanes per plane (the last one may own fewer rows)
+    static constexpr bool RAG = Hout % R != 0;
+    static constexpr int pick_g() {
+        for (int g = 64 / LP; g >= 1; --g)
+            if ((g * HW) % 4 == 0 && (g * HoWo) % 4 == 0) return g;
+        return 0;
+    }
+    static constexpr int G = pick_g();                      // planes per wavefront
+    static constexpr int IN = G * HW, OUT = G * HoWo;       // floats per wavefront
+    static constexpr int NSI = (IN / 4 + 63) / 64, NSO = (OUT / 4 + 63) / 64;
+    static constexpr int NR = (R - 1) * S + 3;              // input rows of a lane's window
+    static constexpr int FRONT = (W + 3) / 4 * 4;           // the first plane's row -1
+    static constexpr int over = (LP * R - 1) * S + 2 - H;   // rows the last window reaches past its plane
+    static constexpr int BACK = (over > 0 ? over : 0) * W;
+    static constexpr int REGION = (FRONT + IN + BACK + 3) / 4 * 4;   // floats per wavefront
+    static constexpr int VR = W % 4 == 0 ? 4 : W % 2 == 0 ? 2 : 1;   // window reads
+    static constexpr int ao = RAG ? Wout : R * Wout;        // floats written at one aligned position
+    static constexpr int VO = (ao % 4 == 0 && HoWo % 4 == 0) ? 4 : (ao % 2 == 0 && HoWo % 2 == 0) ? 2 : 1;
+    // the nine weights of the wave's planes: fetched lane by lane (9 loads), or, when the wave has few planes,
+    // as one flat list of G*9 values through LDS (NWS loads)
+    static constexpr int NWS = (G * 9 + 63) / 64;
+    static constexpr bool COOP = CP < 0 ? NWS <= 4 : CP != 0;
+    static constexpr int WTS = COOP ? (G * 9 + 3) / 4 * 4 : 0;
+    static constexpr int WAVE_FLOATS = REGION + WTS;
+    static_assert(G > 0 && OUT <= IN, "unsupported shape");
+};
+
+struct TileW {
+    unsigned chunks, planes, m_C;
+    unsigned x_bytes, y_bytes, w_bytes;
+};
+
+template <int S, int H, int W, int R, int CP>
+__global__ __launch_bounds__(256) void conv_dw_wave(ConvParams p, TileW t) {
+    using Q = DwWaveGeom<S, H, W, R, CP>;
+    extern __shared__ f32x4 smem4[];
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    const unsigned chunk = blockIdx.x * 4 + wv;
+    if (chunk >= t.chunks) return;   // wave-uniform; the kernel has no barriers
+    float *reg = reinterpret_cast<float *>(smem4) + wv * Q::WAVE_FLOATS;
+    float *data = reg + Q::FRONT;
+    const __amdgpu_buffer_rsrc_t rx = make_rsrc(p.x, t.x_bytes);
+    const __amdgpu_buffer_rsrc_t rw = make_rsrc(p.wd, t.w_bytes);
+
+    // ---- the wave's planes, requested first ----
+    const unsigned gbase = chunk * (unsigned)(Q::IN * 4);
+    f32x4 pin[Q::NSI];
+#pragma unroll
+    for (int j = 0; j < Q::NSI; ++j) {
+        const int q = lane + 64 * j;
+        pin[j] = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(rx, q * 4 < Q::IN ? gbase + q * 16 : kOob, 0, 0));
+    }
+    // ---- the lane's plane, rows and weights ----
+    const bool active = lane < Q::G * Q::LP;
+    const int la = active ? lane : 0;
+    const int pl = Q::LP == 1 ? la : la / Q::LP;
+    const int oh0 = Q::LP == 1 ? 0 : (la - pl * Q::LP) * R;
+    float w[9];
+    if constexpr (Q::COOP) {
+        float *wts = reg + Q::REGION;
+#pragma unroll
+        for (int j = 0; j < Q::NWS; ++j) {
+            const int i = lane + 64 * j;
+            if (i < Q::G * 9) {
+                const int wp = i / 9, k = i - wp * 9;
+                unsigned pg = chunk * Q::G + wp;
+                pg = pg < t.planes ? pg : t.planes - 1;
+                const unsigned c = pg - fast_div(pg, t.m_C) * p.Cin;
+                wts[i] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rw, ((c * 9 + k) * p.KPGd) * 4, 0, 0));
+            }
+        }
+    } else {
+        unsigned pg = chunk * Q::G + pl;
+        pg = pg < t.planes ? pg : t.planes - 1;
+        const unsigned c = pg - fast_div(pg, t.m_C) * p.Cin;
+#pragma unroll
+        for (int k = 0; k < 9; ++k)
+            w[k] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rw, ((c * 9 + k) * p.KPGd) * 4, 0, 0));
+    }
+#pragma unroll
+    for (int j = 0; j < Q::NSI; ++j) {
+        const int q = lane + 64 * j;
+        if (q * 4 < Q::IN) *reinterpret_cast<f32x4 *>(data + q * 4) = pin[j];
+    }
+    asm volatile("" ::: "memory");
+    if constexpr (Q::COOP) {
+        const float *wts = reg + Q::REGION;
+#pragma unroll
+        for (int k = 0; k < 9; ++k) w[k] = wts[pl * 9 + k];
+    }
+    // ---- window: rows oh0*S - 1 .. oh0*S - 1 + NR - 1 of the plane ----
+    float xr[Q::NR][W];
+    {
+        const int ih0 = oh0 * S - 1;
+        const float *wp = data + pl * Q::HW + ih0 * W;
+#pragma unroll
+        for (int i = 0; i < Q::NR; ++i) {
+            const bool valid = (unsigned)(ih0 + i) < (unsigned)H;
+#pragma unroll
+            for (int x = 0; x < W; x += Q::VR) {
+                if constexpr (Q::VR == 4) {
+                    const f32x4 v = *reinterpret_cast<const f32x4 *>(wp + i * W + x);
+                    xr[i][x] = valid ? v.x : 0.f;
+                    xr[i][x + 1] = valid ? v.y : 0.f;
+                    xr[i][x + 2] = valid ? v.z : 0.f;
+                    xr[i][x + 3] = valid ? v.w : 0.f;
+                } else if constexpr (Q::VR == 2) {
+                    const float2 v = *reinterpret_cast<const float2 *>(wp + i * W + x);
+                    xr[i][x] = valid ? v.x : 0.f;
+                    xr[i][x + 1] = valid ? v.y : 0.f;
+                } else {
+                    const float v = wp[i * W + x];
+                    xr[i][x] = valid ? v : 0.f;
+                }
+            }
+        }
+    }
+    asm volatile("" ::: "memory");
+    // ---- R rows of Wout outputs, written to their flat position in the region ----
+    {
+        float *op = data + pl * Q::HoWo + oh0 * Q::Wout;
+        float acc[R * Q::Wout];
+#pragma unroll
+        for (int r = 0; r < R; ++r)
+#pragma unroll
+            for (int ow = 0; ow < Q::Wout; ++ow) {
+                float a = 0.f;
+#pragma unroll
+                for (int kh = 0; kh < 3; ++kh)
+#pragma unroll
+                    for (int kw = 0; kw < 3; ++kw) {
+                        const int col = ow * S - 1 + kw;
+                        if (col >= 0 && col < W) a = fmaf(xr[r * S + kh][col], w[kh * 3 + kw], a);
+                    }
+                acc[r * Q::Wout + ow] = a;
+            }
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            // without ragged rows the lane's R rows are written as one run
+            if (active && (!Q::RAG || oh0 + r < Q::Hout)) {
+#pragma unroll
+                for (int x = 0; x < Q::Wout; x += (Q::RAG ? Q::VO : 1)) {
+                    const int e = r * Q::Wout + x;
+                    if (!Q::RAG && e % Q::VO != 0) continue;
+                    if constexpr (Q::VO == 4) *reinterpret_cast<f32x4 *>(op + e) = f32x4{acc[e], acc[e + 1], acc[e + 2], acc[e + 3]};
+                    else if constexpr (Q::VO == 2) *reinterpret_cast<float2 *>(op + e) = float2{acc[e], acc[e + 1]};
+                    else op[e] = acc[e];
+                }
+            }
+        }
+    }
+    asm volatile("" ::: "memory");
+    // ---- flat read-back, residual, ReLU, 16-byte stores ----
+    const __amdgpu_buffer_rsrc_t ry = make_rsrc(p.y, t.y_bytes);
+    const __amdgpu_buffer_rsrc_t rr = make_rsrc(p.res ? p.res : p.y, t.y_bytes);
+    const unsigned obase = chunk * (unsigned)(Q::OUT * 4);
+#pragma unroll
+    for (int j = 0; j < Q::NSO; ++j) {
+        const int q = lane + 64 * j;
+        if (q * 4 < Q::OUT) {
+            f32x4 v = *reinterpret_cast<const f32x4 *>(data + q * 4);
+            if (p.res) v += __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(rr, obase + q * 16, 0, 0));
+            if (p.relu) v = f32x4{fmaxf(v.x, 0.f), fmaxf(v.y, 0.f), fmaxf(v.z, 0.f), fmaxf(v.w, 0.f)};
+            __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, v), ry, obase + q * 16, 0, 0);
+        }
+    }
+}
+
+constexpr int kDwKind = 23, kDwInst = 22;   // plan slots: 1 = whole planes per wavefront, and its instance
+
+// Instances of conv_dw_wave: (stride, plane edge, output rows per lane, weights through LDS), each the fastest of
+// the forms measured at N = 256 (one row per lane except on 7x7 planes at stride 2; the 56x56 stride-2 layer
+// is faster on the strip kernel and has no instance).
+template <int I> struct DwWaveInst;
+#define GSPC_DW_WAVE_INST(I, S_, E_, R_, CP_) \
+    template <> struct DwWaveInst<I> { using Q = DwWaveGeom<S_, E_, E_, R_, CP_>; static constexpr int S = S_, E = E_, R = R_, CP = CP_; }
+GSPC_DW_WAVE_INST(0, 1, 28, 1, 0);
+GSPC_DW_WAVE_INST(1, 2, 28, 1, 0);
+GSPC_DW_WAVE_INST(2, 1, 14, 1, 0);
+GSPC_DW_WAVE_INST(3, 2, 14, 1, 0);
+GSPC_DW_WAVE_INST(4, 1, 7, 1, 1);
+GSPC_DW_WAVE_INST(5, 2, 7, 2, 0);
+GSPC_DW_WAVE_INST(6, 1, 56, 1, 0);
+constexpr int kDwWaveInsts = 7;
+
+template <int I>
+bool plan_dw_wave_inst(const ConvParams &p, DwPlan *out) {
+    using T = DwWaveInst<I>;
+    using Q = typename T::Q;
+    if (p.stride != T::S || p.H != T::E || p.W != T::E) return false;
+    const double planes = (double)p.N * p.Cin;
+    const double chunks = (planes + Q::G - 1) / Q::G;
+    // small launches stay on the block form, which shrinks its tiles to spread over the chip
+    static const bool force = std::getenv("GSPC_DW_WAVE") != nullptr;   // tuning aid
+    if (!force && chunks < 4.0 * 2 * kNumCU) return false;
+    const double xb = planes * Q::HW * 4, yb = planes * Q::HoWo * 4, wb = (double)p.groups * 9 * p.KPGd * 4;
+    const double slack = 4.0 * Q::IN * 4 + 65536;   // offsets past the tensor's end must not wrap
+    if (planes >= 2147483648.0 || xb + slack >= (double)kOob || yb + slack >= (double)kOob || wb >= (double)kOob ||
+        planes * p.Cin >= 4.29e9)
+        return false;
+    TileW t{};
+    t.planes = (unsigned)planes;
+    t.chunks = (unsigned)((t.planes + Q::G - 1) / Q::G);
+    t.m_C = div_magic(p.Cin);
+    t.x_bytes = (unsigned)xb;
+    t.y_bytes = (unsigned)yb;
+    t.w_bytes = (unsigned)wb;
+    static_assert(sizeof(TileW) <= sizeof(int) * kDwInst, "plan storage too small");
+    std::memcpy(out->data, &t, sizeof(t));
+    out->data[kDwKind] = 1;
+    out->data[kDwInst] = I;
+    return true;
+}
+
+template <int I = 0>
+bool plan_dw_wave(const ConvParams &p, DwPlan *out) {
+    static const bool off = std::getenv("GSPC_NO_DWWAVE") != nullptr;   // tuning aid
+    if (off) return false;
+    if constexpr (I < kDwWaveInsts) return plan_dw_wave_inst<I>(p, out) || plan_dw_wave<I + 1>(p, out);
+    else return false;
+}
+
+template <int I = 0>
+hipError_t launch_dw_wave(int inst, const ConvParams &p, const TileW &t, hipStream_t s, const char **name) {
+    if constexpr (I < kDwWaveInsts) {
+        if (inst != I) return launch_dw_wave<I + 1>(inst, p, t, s, name);
+        using T = DwWaveInst<I>;
+        using Q = typename T::Q;
+        *name = intern_name("conv_dw_wave<" + std::to_string(T::S) + "," + std::to_string(T::E) + "," + std::to_string(T::E) +
+                            "," + std::to_string(T::R) + "," + std::to_string(T::CP) + ">");
+        const size_t lds = (size_t)4 * Q::WAVE_FLOATS * sizeof(float);
+        hipLaunchKernelGGL((conv_dw_wave<T::S, T::E, T::E, T::R, T::CP>), dim3((t.chunks + 3) / 4), dim3(256), lds, s, p, t);
+        return hipGetLastError();
+    } else {
+        return hipErrorNotSupported;
+    }
+}
+
 bool plan_dw_planes(const ConvParams &p, DwPlan *out) {
     static const bool off = std::getenv("GSPC_NO_DWPLANES") != nullptr;   // tuning aid
     if (off || p.CPG != 1 || p.KPG != 1 || p.in_bf16 || p.KH != 3 || p.KW != 3 || p.pad != 1 ||
         (p.stride != 1 && p.stride != 2))
         return false;
+    if (plan_dw_wave(p, out)) return true;
+    out->data[kDwKind] = 0;
     TileD t{};
     t.LWp = p.W + 2;
     t.PL = round_up((p.H + 2) * t.LWp, 4);
@@ -215,7 +479,7 @@ bool plan_dw_planes(const ConvParams &p, DwPlan *out) {
     t.x_bytes = (unsigned)xb;
     t.y_bytes = (unsigned)yb;
     t.w_bytes = (unsigned)wb;
-    static_assert(sizeof(TileD) <= sizeof(out->data), "plan storage too small");
+    static_assert(sizeof(TileD) <= sizeof(int) * kDwInst, "plan storage too small");
     std::memcpy(out->data, &t, sizeof(t));
     return true;
 }
@@ -241,6 +505,11 @@ inline int dw_row_width(const ConvParams &p) {
 }  // namespace
 
 hipError_t launch_dw_planes(const ConvParams &p, const DwPlan &plan, hipStream_t s, const char **name) {
+    if (plan.data[kDwKind] == 1) {
+        TileW tw;
+        std::memcpy(&tw, plan.data, sizeof(tw));
+        return launch_dw_wave(plan.data[kDwInst], p, tw, s, name);
+    }
     TileD t;
     std::memcpy(&t, plan.data, sizeof(t));
     const int wt = dw_row_width(p);

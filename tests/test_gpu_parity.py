@@ -141,6 +141,39 @@ def test_depthwise_pairs(gpu):
         check(gpu, pw, seed=wl.make_seed(4, 2 * i + 1, 1))
 
 
+DW_WAVE = [   # (N, C, plane edge, stride): enough planes for the whole-planes-per-wavefront kernel, ragged last wavefront
+    (17, 129, 56, 1), (33, 129, 28, 1), (63, 131, 28, 2), (37, 521, 14, 1), (33, 521, 14, 2), (129, 1031, 7, 1), (129, 1031, 7, 2),
+]
+
+
+@pytest.mark.parametrize("N,C,hw,stride", DW_WAVE, ids=lambda v: str(v))
+def test_depthwise_whole_planes_per_wavefront(gpu, N, C, hw, stride):
+    """Depthwise 3x3 on 28x28, 14x14 and 7x7 planes at batches that fill the chip: whole tensors against the
+    oracle, plane count not a multiple of a wavefront's share; then the same layer with residual and ReLU in a chain."""
+    torch, b = gpu
+    from helpers import gpu_chain, oracle_chain
+    s = S(N, C, hw, hw, C, 3, 3, stride, 1, C)
+    name = check(gpu, s, seed=wl.make_seed(4, 700 + hw, stride))
+    assert name.startswith(f"conv_dw_wave<{stride},{hw},{hw},"), name
+    ho = (hw - 1) // stride + 1
+    ch = wl.Chain("dwres", (N, C, hw, hw))
+    ch.conv(0, 1, N, C, hw, hw, C, 3, stride, 1, C, relu=True)
+    ch.conv(0, 2, N, C, hw, hw, C, 3, stride, 1, C, relu=True, residual=1)
+    ch.conv(0, 3, N, C, hw, hw, C, 3, stride, 1, C, residual=2)
+    x0 = wl.make_input(ch.input_shape, 91)
+    weights = ch.make_weights(17)
+    ref = oracle_chain(ch, x0, weights, threads=8)
+    lc, bufs = gpu_chain(ch, x0, weights)
+    for bf in bufs[1:]:
+        bf.fill_(float("nan"))
+    b.gspc_run_layer_chain(lc)
+    torch.cuda.synchronize()
+    assert b.gspc_last_kernel().startswith("conv_dw_wave<"), b.gspc_last_kernel()
+    for i in (1, 2, 3):
+        got = bufs[i][:N * C * ho * ho].cpu().numpy().reshape(ref[i].shape)
+        assert rel_err(got, ref[i]) < TOL_F32, i
+
+
 def test_pack_is_a_permutation(gpu):
     torch, b = gpu
     dev = torch.device("cuda:0")
