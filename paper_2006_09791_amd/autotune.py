@@ -27,7 +27,7 @@ from . import workloads as wl
 FAMILIES = {
     "w": ("conv_mfma16w<", range(5)),
     "m": ("conv_mfma16<", range(13)),
-    "b": ("conv_mfma16b<", range(6)),
+    "b": ("conv_mfma16b<", range(7)),
     "q": ("conv_mfma4r<", (1, 2, 4)),
     "x": ("conv_wino<", range(7)),      # Winograd F(2x2, 3x3): fp32, 3x3, stride 1, pad 1
     "r": ("conv_row16", range(9)),      # bf16 row products: 3x3, stride 1, pad 1, at most 16 channels per group

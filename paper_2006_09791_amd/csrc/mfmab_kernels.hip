@@ -43,7 +43,11 @@ static_assert(sizeof(TileB) <= sizeof(((MfmaB16Plan *)0)->data), "plan storage t
 // there Wout is a multiple of 4 for a 3x3 window with padding 1 (Wout = W / stride).
 constexpr bool always_vec_out(int vw, int stride) { return stride == 1 ? vw >= 4 : vw == 8; }
 
-constexpr int kTmaxB = 4, kWmaxB = 6;   // staging slots per thread (half as many with 8-pixel tasks)
+constexpr int kTmaxB = 4, kWmaxB = 9;
+#ifndef GSPC_WAIT_STORES
+#define GSPC_WAIT_STORES 1
+#endif
+constexpr bool kWaitStores = GSPC_WAIT_STORES;   // staging slots per thread (half as many with 8-pixel tasks)
 
 #ifdef GSPC_PHASE_TIMING
 __device__ unsigned long long g_phase_b[8 * 4096];
@@ -238,7 +242,11 @@ __global__ __launch_bounds__(64 * WM * WP, 2) void conv_mfma16b(ConvParams p, Ti
     const __amdgpu_buffer_rsrc_t rr = make_rsrc(p.res ? p.res : p.y, t.y_bytes);
     const unsigned oc0 = (ob * MIWM + wm * MI) * 16;
 
-    unsigned tg = blockIdx.x;
+    // Tiles in XCD-aware order: workgroups go to the chip's eight XCDs (each with its own L2) in turn,
+    // so the blocks of one XCD are given neighbouring tiles - bands of the same image, whose halo rows
+    // then meet in that L2 instead of being fetched from memory once per XCD.
+    const unsigned bx0 = (gridDim.x & 7) == 0 ? (blockIdx.x & 7) * (gridDim.x >> 3) + (blockIdx.x >> 3) : blockIdx.x;
+    unsigned tg = bx0;
     int ch = 0;
     unsigned xo_n[TMAX];
     TileU tu_n, tu;
@@ -249,7 +257,7 @@ __global__ __launch_bounds__(64 * WM * WP, 2) void conv_mfma16b(ConvParams p, Ti
     unsigned long long phase_clk[8] = {0, 0, 0, 0, 0, 0, 0, 0}, phase_t = __builtin_amdgcn_s_memtime();
 #endif
     for (;;) {
-        const bool first = tg == blockIdx.x;
+        const bool first = tg == bx0;
         if (ch == 0) tu = tu_n;
         __syncthreads();   // everyone is done reading the previous step's tile
         GSPC_CLKB(0)
@@ -289,7 +297,7 @@ __global__ __launch_bounds__(64 * WM * WP, 2) void conv_mfma16b(ConvParams p, Ti
         if (ch == 0 && !first_step) {
             // a new tile: wait for the previous tile's stores (nothing else is in flight
             // here), then clear the accumulators they read from
-            __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
+            if (kWaitStores) __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
 #pragma unroll
             for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
@@ -300,12 +308,16 @@ __global__ __launch_bounds__(64 * WM * WP, 2) void conv_mfma16b(ConvParams p, Ti
                 }
         }
         first_step = false;
-        prefetch(xo_n, nch, more && (!t.wres || ntg == blockIdx.x));
+        prefetch(xo_n, nch, more && (!t.wres || ntg == bx0));
         __builtin_amdgcn_sched_barrier(0);
         GSPC_CLKB(3)
         // ---- multiply: the operands of k-step s+1 are read from LDS while the matrix
         // unit works on k-step s ----
-        bf16x8 opa[2][MI], opb[2][NI];
+        // (a wave tile of sixteen MFMAs per k-step would keep one operand set: a second one does not fit the
+        // register file; no such instance is built at present - with its staging registers the 64 x 64 tile
+        // spills even so, and ran at half the speed of the 32 x 64 one)
+        constexpr bool DB = MI * NI < 16;
+        bf16x8 opa[DB ? 2 : 1][MI], opb[DB ? 2 : 1][NI];
         auto load_ops = [&](int ks, int set) {
 #pragma unroll
             for (int mi = 0; mi < MI; ++mi)
@@ -314,17 +326,20 @@ __global__ __launch_bounds__(64 * WM * WP, 2) void conv_mfma16b(ConvParams p, Ti
             for (int ni = 0; ni < NI; ++ni)
                 opb[set][ni] = *reinterpret_cast<const bf16x8 *>(xs + pixb[ni] + unit_off(ks));
         };
-        load_ops(0, 0);
+        if (DB) load_ops(0, 0);
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
-            if (ks + 1 < KS) load_ops(ks + 1, (ks + 1) & 1);
+            if (!DB) load_ops(ks, 0);
+            else if (ks + 1 < KS) load_ops(ks + 1, (ks + 1) & 1);
             __builtin_amdgcn_sched_barrier(0);
+            constexpr int dummy = 0;
+            const int set = DB ? (ks & 1) : dummy;
 #pragma unroll
             for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
                 for (int ni = 0; ni < NI; ++ni)
-                    acc[mi][ni] = VO ? __builtin_amdgcn_mfma_f32_16x16x32_bf16(opb[ks & 1][ni], opa[ks & 1][mi], acc[mi][ni], 0, 0, 0)
-                                     : __builtin_amdgcn_mfma_f32_16x16x32_bf16(opa[ks & 1][mi], opb[ks & 1][ni], acc[mi][ni], 0, 0, 0);
+                    acc[mi][ni] = VO ? __builtin_amdgcn_mfma_f32_16x16x32_bf16(opb[set][ni], opa[set][mi], acc[mi][ni], 0, 0, 0)
+                                     : __builtin_amdgcn_mfma_f32_16x16x32_bf16(opa[set][mi], opb[set][ni], acc[mi][ni], 0, 0, 0);
             __builtin_amdgcn_sched_barrier(0);
         }
         GSPC_CLKB(4)
@@ -426,7 +441,7 @@ constexpr int kLdsResB = 80 * 1024;      // with every chunk's filters: two bloc
 struct CfgB {
     int MI, NI, WM, WP;
 };
-const CfgB kCfgB[] = {{2, 4, 1, 4}, {1, 4, 1, 4}, {2, 2, 1, 4}, {1, 2, 1, 4}, {2, 1, 1, 4}, {1, 1, 1, 4}};
+const CfgB kCfgB[] = {{2, 4, 1, 4}, {1, 4, 1, 4}, {2, 2, 1, 4}, {1, 2, 1, 4}, {2, 1, 1, 4}, {1, 1, 1, 4}, {4, 2, 1, 4}};
 constexpr int kNumCfgB = sizeof(kCfgB) / sizeof(kCfgB[0]);
 
 int vw_of(int W) { return W % 8 == 0 ? 8 : W % 4 == 0 ? 4 : W % 2 == 0 ? 2 : 1; }
@@ -434,6 +449,7 @@ int vw_of(int W) { return W % 8 == 0 ? 8 : W % 4 == 0 ? 4 : W % 2 == 0 ? 2 : 1; 
 bool planB_cfg(const ConvParams &p, const PackGeom &g, const CfgB &c, TileB *out) {
     const int MB = 16 * c.MI * c.WM, PB = 16 * c.NI * c.WP, NT = 64 * c.WM * c.WP;
     if ((g.mtiles_b * 16) % MB) return false;
+    if (c.MI == 4 && g.ckb != 32) return false;
     TileB t{};
     if (!split_pixels(p, PB, &t.NB, &t.TH)) return false;
     t.IHt = (t.TH - 1) * p.stride + 3;
@@ -483,6 +499,7 @@ bool planB_cfg(const ConvParams &p, const PackGeom &g, const CfgB &c, TileB *out
         cap = cap < 1 ? 1 : cap;
         const long rounds = (t.tiles + cap - 1) / cap;
         t.gx = (int)((t.tiles + rounds - 1) / rounds);
+        if (t.gx >= 8) t.gx = round_up(t.gx, 8);   // the kernel's XCD-aware tile order wants a multiple of 8
     }
     *out = t;
     return true;
@@ -526,8 +543,12 @@ hipError_t launchB_vw(int vw, const ConvParams &p, const TileB &t, hipStream_t s
 template <int MI, int NI, int WM, int WP, int S>
 hipError_t launchB_ckb(int ckb, int vw, const ConvParams &p, const TileB &t, hipStream_t s) {
     if (ckb == 32) return launchB_vw<MI, NI, WM, WP, S, 32>(vw, p, t, s);
-    if (ckb == 16) return launchB_vw<MI, NI, WM, WP, S, 16>(vw, p, t, s);
-    return launchB_vw<MI, NI, WM, WP, S, 8>(vw, p, t, s);
+    if constexpr (MI == 4) {   // 64 filters per block: built for the 32-channel chunks of wide groups only
+        return hipErrorNotSupported;
+    } else {
+        if (ckb == 16) return launchB_vw<MI, NI, WM, WP, S, 16>(vw, p, t, s);
+        return launchB_vw<MI, NI, WM, WP, S, 8>(vw, p, t, s);
+    }
 }
 
 template <int MI, int NI, int WM, int WP>
@@ -562,9 +583,22 @@ bool plan_mfma_bf16(const ConvParams &p0, const PackGeom &g, MfmaB16Plan *out) {
     int best = -1;
     long best_blocks = -1;
     TileB bt{};
+    // Planes of up to 8 x 8 pixels (several images per tile, so a tile's staging is all halo and index
+    // work): 64 filters per block halve the staging per multiplication (the 512-channel 7x7 layers at
+    // N = 256: 62 -> 46 us for g = 2, 20 -> 18 us for g = 8; on 14 x 14 planes and up it changes nothing).
+    if (forced < 0 && p.H * p.W <= 64) {
+        TileB t;
+        if (planB_cfg(p, g, kCfgB[kNumCfgB - 1], &t) &&
+            (long)t.row_blocks * t.img_blocks * t.oc_blocks * p.groups >= 4 * kNumCU) {
+            out->inst = kNumCfgB - 1;
+            std::memcpy(out->data, &t, sizeof(t));
+            return true;
+        }
+    }
     for (int i = 0; i < kNumCfgB; ++i) {
         TileB t;
         if (forced >= 0 && forced != i) continue;
+        if (forced < 0 && kCfgB[i].MI == 4) continue;   // only by the rule above or when asked for
         if (!planB_cfg(p, g, kCfgB[i], &t)) continue;
         const long blocks = (long)t.row_blocks * t.img_blocks * t.oc_blocks * p.groups;
         if (blocks >= 4 * kNumCU) {
@@ -602,6 +636,7 @@ hipError_t launch_mfma_bf16(const ConvParams &p0, const PackGeom &g, const MfmaB
     case 3: return launchB_s<1, 2, 1, 4>(g.ckb, vw, p, t, s);
     case 4: return launchB_s<2, 1, 1, 4>(g.ckb, vw, p, t, s);
     case 5: return launchB_s<1, 1, 1, 4>(g.ckb, vw, p, t, s);
+    case 6: return launchB_s<4, 2, 1, 4>(g.ckb, vw, p, t, s);
     }
     return hipErrorNotSupported;
 }
