@@ -3,7 +3,8 @@
 Each layer is replayed back to back inside one recorded layer chain (no host in
 the loop) and timed with events on the launch stream.  Returns rows with the
 Eq. 2 MAC count, the algorithmic bytes and the fractions of the nominal MI355X
-ceilings (fp32 MFMA 157.3 TFLOP/s, bf16 MFMA 2500 TFLOP/s, HBM 8 TB/s).
+ceilings (fp32 MFMA 157.3 TFLOP/s, bf16 MFMA 2500 TFLOP/s, HBM 8 TB/s).  Rows of the
+Winograd kernel report the executed multiplications (16/36 of Eq. 2's) against the peak.
 """
 import numpy as np
 
@@ -58,13 +59,19 @@ def time_layers(shapes, dtype="f32", inner=10, reps=10, rotate=1):
         us = e0.elapsed_time(e1) / (reps * inner) * 1e3
         macs = wl.conv_macs(s)
         nbytes = layer_bytes(s, 2 if dtype == "bf16" else 4)
-        rows.append({
+        row = {
             "layer": f"{s.Cin}->{s.Cout} {s.H}x{s.W} k{s.KH} s{s.stride} g{s.groups} N{s.N}",
             "kernel": name, "us": round(us, 2), "gmacs": round(macs / us / 1e3, 1),
             "tflops": round(2 * macs / us / 1e6, 2), "gbs": round(nbytes / us / 1e3, 1),
             "frac_mfma": round(2 * macs / us / 1e6 / PEAK_TFLOPS[dtype], 4),
             "frac_hbm": round(nbytes / us / 1e3 / PEAK_HBM_GBS, 4),
-        })
+        }
+        if name.startswith("conv_wino"):
+            # Winograd F(2x2, 3x3) executes 16/36 of the multiplications Eq. 2 counts: `tflops` is an
+            # effective rate (no fraction of a peak belongs to it), `frac_mfma` the executed work's share
+            row["algorithm"] = "winograd"
+            row["frac_mfma"] = round(row["frac_mfma"] * 16.0 / 36.0, 4)
+        rows.append(row)
         del bufs, lc
     b.gspc_set_chain_fusion(1)
     return rows

@@ -22,6 +22,20 @@ def rel_err(got, ref):
     return float(np.max(np.abs(got - ref) / den))
 
 
+def err_metrics(got, ref, absum=None):
+    """The error of a tensor three ways: 'floored' is rel_err (the metric the tolerances are stated in),
+    'scaled' = max|g - r| / max|r|, and, when the oracle's sum |x*w| per output is given, 'bound' =
+    max_i |g_i - r_i| / A_i, the quantity the textbook bound |fl(s) - s| <= gamma_K * A speaks about."""
+    got = np.asarray(got, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    out = {"floored": rel_err(got, ref), "scaled": 0.0}
+    if ref.size:
+        out["scaled"] = float(np.max(np.abs(got - ref)) / max(float(np.max(np.abs(ref))), 1e-30))
+    if absum is not None and ref.size:
+        out["bound"] = float(np.max(np.abs(got - ref) / np.maximum(np.asarray(absum, dtype=np.float64), 1e-30)))
+    return out
+
+
 def oracle_chain(chain, x0, weights, threads=8):
     """Runs a workloads.Chain with the CPU oracle, all in float64."""
     return oracle.run_chain(chain.layers, len(chain.buf_elems), x0, weights, threads=threads)
