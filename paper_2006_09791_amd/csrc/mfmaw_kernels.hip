@@ -215,6 +215,35 @@ __global__ __launch_bounds__(256) void conv_mfma16w(ConvParams p, Tile16w t) {
             for (int ni = 0; ni < NI; ++ni) b[kw][ni] = xrow[base[ni] + kw];
         }
     };
+    // One k-step (tap kw of a row) of operands, and of MFMAs.
+    auto load_kw = [&](int ch, int row, int kw, float (&a)[3][MI], float (&b)[3][NI]) __attribute__((always_inline)) {
+        const int cb = row / 3, kh = row - 3 * cb;
+        const float *xrow = ring + (ch & 1) * t.stage_floats + cb * 4 * t.PLANE + kh * t.LW;
+        const float *ws = smem + (ch * KCHUNK + row * 3) * (MI * 64) + lane;
+#pragma unroll
+        for (int mi = 0; mi < MI; ++mi) a[kw][mi] = ws[(kw * MI + mi) * 64];
+#pragma unroll
+        for (int ni = 0; ni < NI; ++ni) b[kw][ni] = xrow[base[ni] + kw];
+    };
+    auto mfma_kw = [&](int kw, const float (&a)[3][MI], const float (&b)[3][NI]) __attribute__((always_inline)) {
+#pragma unroll
+        for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+            for (int ni = 0; ni < NI; ++ni)
+                acc[mi][ni] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[kw][mi], b[kw][ni], acc[mi][ni], 0, 0, 0);
+    };
+    // Row i multiplied while row i+1 (chunk nch, row nrow) is read: the reads of a tap follow that tap's MFMAs, so
+    // they issue while the matrix unit works; a burst of all reads in front of the row's MFMAs left the unit idle
+    // for the time the burst takes to issue, every row.
+    auto step_row = [&](const float (&a)[3][MI], const float (&b)[3][NI], int nch, int nrow, float (&na)[3][MI],
+                        float (&nb)[3][NI]) __attribute__((always_inline)) {
+#pragma unroll
+        for (int kw = 0; kw < 3; ++kw) {
+            mfma_kw(kw, a, b);
+            load_kw(nch, nrow, kw, na, nb);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
     auto mfma_row = [&](const float (&a)[3][MI], const float (&b)[3][NI]) __attribute__((always_inline)) {
 #pragma unroll
         for (int kw = 0; kw < 3; ++kw)
@@ -242,17 +271,11 @@ __global__ __launch_bounds__(256) void conv_mfma16w(ConvParams p, Tile16w t) {
         load_row(0, 0, opa[0], opb[0]);
 #pragma unroll
         for (int i = 0; i < R; ++i) {
-            if (i + 1 < R) load_row(0, i + 1, opa[(i + 1) & 1], opb[(i + 1) & 1]);
-            __builtin_amdgcn_sched_barrier(0);   // operand reads first, then the MFMAs they overlap with
 #pragma unroll
             for (int kw = 0; kw < 3; ++kw) {
+                mfma_kw(kw, opa[i & 1], opb[i & 1]);
                 fetch_w(W0 + (i * 3 + kw) * PER, W0 + (i * 3 + kw + 1) * PER);
-#pragma unroll
-                for (int mi = 0; mi < MI; ++mi)
-#pragma unroll
-                    for (int ni = 0; ni < NI; ++ni)
-                        acc[mi][ni] = __builtin_amdgcn_mfma_f32_16x16x4f32(opa[i & 1][kw][mi], opb[i & 1][kw][ni],
-                                                                           acc[mi][ni], 0, 0, 0);
+                if (i + 1 < R) load_kw(0, i + 1, kw, opa[(i + 1) & 1], opb[(i + 1) & 1]);
                 __builtin_amdgcn_sched_barrier(0);
             }
         }
@@ -285,14 +308,12 @@ __global__ __launch_bounds__(256) void conv_mfma16w(ConvParams p, Tile16w t) {
 #pragma unroll
         for (int i = 0; i < R; ++i) {
             if (i + 1 < R) {
-                load_row(ch, i + 1, opa[(P1 + i + 1) & 1], opb[(P1 + i + 1) & 1]);
+                step_row(opa[(P1 + i) & 1], opb[(P1 + i) & 1], ch, i + 1, opa[(P1 + i + 1) & 1], opb[(P1 + i + 1) & 1]);
             } else {
                 if (ch + 1 < t.nchunks) commit_x(0, pin0);
-                load_row(ch + 1, 0, opa[(P1 + i + 1) & 1], opb[(P1 + i + 1) & 1]);
+                __builtin_amdgcn_sched_barrier(0);
+                step_row(opa[(P1 + i) & 1], opb[(P1 + i) & 1], ch + 1, 0, opa[(P1 + i + 1) & 1], opb[(P1 + i + 1) & 1]);
             }
-            __builtin_amdgcn_sched_barrier(0);
-            mfma_row(opa[(P1 + i) & 1], opb[(P1 + i) & 1]);
-            __builtin_amdgcn_sched_barrier(0);
         }
         if (ch + 1 < t.nchunks) {
             // even chunk: pin0 is free, pin1 holds chunk ch+2
@@ -300,14 +321,12 @@ __global__ __launch_bounds__(256) void conv_mfma16w(ConvParams p, Tile16w t) {
 #pragma unroll
             for (int i = 0; i < R; ++i) {
                 if (i + 1 < R) {
-                    load_row(ch + 1, i + 1, opa[(i + 1) & 1], opb[(i + 1) & 1]);
+                    step_row(opa[i & 1], opb[i & 1], ch + 1, i + 1, opa[(i + 1) & 1], opb[(i + 1) & 1]);
                 } else {
                     if (ch + 2 < t.nchunks) commit_x(1, pin1);
-                    load_row(ch + 2, 0, opa[(i + 1) & 1], opb[(i + 1) & 1]);
+                    __builtin_amdgcn_sched_barrier(0);
+                    step_row(opa[i & 1], opb[i & 1], ch + 2, 0, opa[(i + 1) & 1], opb[(i + 1) & 1]);
                 }
-                __builtin_amdgcn_sched_barrier(0);
-                mfma_row(opa[i & 1], opb[i & 1]);
-                __builtin_amdgcn_sched_barrier(0);
             }
         }
     }
@@ -382,14 +401,12 @@ __global__ __launch_bounds__(256) void conv_mfma16w(ConvParams p, Tile16w t) {
 #pragma unroll
         for (int i = 0; i < R; ++i) {
             if (i + 1 < R) {
-                load_row(0, i + 1, opa[(i + 1) & 1], opb[(i + 1) & 1]);
+                step_row(opa[i & 1], opb[i & 1], 0, i + 1, opa[(i + 1) & 1], opb[(i + 1) & 1]);
             } else {
                 if (t.nchunks > 1) commit_x(1, pin1);
-                load_row(1, 0, opa[(i + 1) & 1], opb[(i + 1) & 1]);
+                __builtin_amdgcn_sched_barrier(0);
+                step_row(opa[i & 1], opb[i & 1], 1, 0, opa[(i + 1) & 1], opb[(i + 1) & 1]);
             }
-            __builtin_amdgcn_sched_barrier(0);
-            mfma_row(opa[i & 1], opb[i & 1]);
-            __builtin_amdgcn_sched_barrier(0);
         }
         steady();
     }
