@@ -16,8 +16,9 @@
 //
 // Launches that fill the chip on 56x56, 28x28, 14x14 and 7x7 planes take conv_dw_wave instead
 // (further down): whole planes per wavefront, no block-level barrier, every global and almost
-// every LDS access 16 bytes wide.  The block form above keeps the small launches (it shrinks its
-// tiles to spread over the chip) and the other plane sizes.
+// every LDS access 16 bytes wide; on 112x112 planes conv_dw_band does the same with a band of 16
+// rows per wavefront.  The block form above keeps the small launches (it shrinks its tiles to
+// spread over the chip) and the other plane sizes.
 #include <cstdlib>
 #include <cstring>
 
@@ -433,12 +434,198 @@ hipError_t launch_dw_wave(int inst, const ConvParams &p, const TileW &t, hipStre
     }
 }
 
+// ---- bands of rows per wavefront (planes too large for the form above) ---------------------------
+// The same scheme for one band of BR output rows of one plane per wavefront: the (BR-1)*S + 3 input rows the
+// band needs are contiguous in memory and are copied flat (the rows above the first and below the last band are
+// other planes' rows, or lie outside the tensor and arrive as zeros: either way they are selected to zero).  A lane
+// owns CW = Wout / NQ consecutive outputs of one row; its 3-row window is read with aligned 8- or 16-byte LDS reads
+// that start VR floats to the left of its first column, the columns left of the plane and right of it are selected
+// to zero.  The plane's nine weights are uniform over the wavefront and sit in scalar registers.
+template <int S, int H, int W, int BR, int NQ>
+struct DwBandGeom {
+    static constexpr int Hout = (H - 1) / S + 1, Wout = (W - 1) / S + 1;
+    static constexpr int NBD = Hout / BR;                    // bands per plane
+    static constexpr int CW = Wout / NQ;                     // outputs per lane
+    static constexpr int NRB = (BR - 1) * S + 3;             // input rows per band
+    static constexpr int IN = NRB * W, OUT = BR * Wout;      // floats per band
+    static constexpr int NSI = (IN / 4 + 63) / 64, NSO = (OUT / 4 + 63) / 64;
+    static constexpr int VR = (CW * S) % 4 == 0 ? 4 : 2;     // alignment (floats) of a lane's first column
+    static constexpr int WIN = (CW - 1) * S + 3;             // window columns
+    static constexpr int XW = (VR - 1 + WIN + VR - 1) / VR * VR;   // floats read per window row
+    static constexpr int REGION = (VR + IN + XW + 3) / 4 * 4;
+    static constexpr int VO = CW % 4 == 0 ? 4 : CW % 2 == 0 ? 2 : 1;
+    static_assert(Hout % BR == 0 && Wout % NQ == 0 && BR * NQ <= 64 && W % 4 == 0 && OUT % 4 == 0 &&
+                      (Hout * Wout) % 4 == 0 && (CW * S) % 2 == 0 && VR >= 2,
+                  "unsupported band shape");
+};
+
+template <int S, int H, int W, int BR, int NQ>
+__global__ __launch_bounds__(256) void conv_dw_band(ConvParams p, TileW t) {
+    using Q = DwBandGeom<S, H, W, BR, NQ>;
+    extern __shared__ f32x4 smem4[];
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    const unsigned chunk = __builtin_amdgcn_readfirstlane(blockIdx.x * 4 + wv);
+    if (chunk >= t.chunks) return;   // wave-uniform; the kernel has no barriers
+    float *data = reinterpret_cast<float *>(smem4) + wv * Q::REGION + Q::VR;
+    const unsigned plane = chunk / Q::NBD, band = chunk - plane * Q::NBD;
+    const __amdgpu_buffer_rsrc_t rx = make_rsrc(p.x, t.x_bytes);
+
+    // ---- the band's input rows, requested first (the row above the first band of the first plane has a
+    // "negative" offset, which wraps to out of range and reads as zero) ----
+    const int ihb = (int)band * (BR * S) - 1;   // first input row of the band
+    const unsigned gbase = (plane * (unsigned)(H * W) + (unsigned)(ihb * W)) * 4u;
+    f32x4 pin[Q::NSI];
+#pragma unroll
+    for (int j = 0; j < Q::NSI; ++j) {
+        const int q = lane + 64 * j;
+        pin[j] = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(rx, q * 4 < Q::IN ? gbase + q * 16 : kOob, 0, 0));
+    }
+    // ---- weights: uniform over the wave ----
+    float w[9];
+    {
+        const unsigned c = plane - fast_div(plane, t.m_C) * p.Cin;
+#pragma unroll
+        for (int k = 0; k < 9; ++k) w[k] = p.wd[(c * 9 + k) * p.KPGd];
+    }
+    const bool active = lane < BR * NQ;
+    const int la = active ? lane : 0;
+    const int r = la / NQ, qs = la - r * NQ;
+#pragma unroll
+    for (int j = 0; j < Q::NSI; ++j) {
+        const int q = lane + 64 * j;
+        if (q * 4 < Q::IN) *reinterpret_cast<f32x4 *>(data + q * 4) = pin[j];
+    }
+    asm volatile("" ::: "memory");
+    // ---- window: 3 rows x XW floats from column qs*CW*S - VR ----
+    float acc[Q::CW];
+#pragma unroll
+    for (int x = 0; x < Q::CW; ++x) acc[x] = 0.f;
+    {
+        const float *wp = data + (r * S) * W + qs * (Q::CW * S) - Q::VR;
+#pragma unroll
+        for (int kh = 0; kh < 3; ++kh) {
+            const bool rvalid = (unsigned)(ihb + r * S + kh) < (unsigned)H;
+            float xr[Q::XW];
+#pragma unroll
+            for (int x = 0; x < Q::XW; x += Q::VR) {
+                if constexpr (Q::VR == 4) {
+                    const f32x4 v = *reinterpret_cast<const f32x4 *>(wp + kh * W + x);
+                    xr[x] = v.x;
+                    xr[x + 1] = v.y;
+                    xr[x + 2] = v.z;
+                    xr[x + 3] = v.w;
+                } else {
+                    const float2 v = *reinterpret_cast<const float2 *>(wp + kh * W + x);
+                    xr[x] = v.x;
+                    xr[x + 1] = v.y;
+                }
+            }
+            // window column j is xr[j + VR - 1]; column 0 lies left of the plane for the first segment, the last one
+            // right of it for the last segment of a stride-1 row
+#pragma unroll
+            for (int j = 0; j < Q::WIN; ++j) {
+                bool ok = rvalid;
+                if (j == 0) ok = ok && qs != 0;
+                if (S == 1 && j == Q::WIN - 1) ok = ok && qs != NQ - 1;
+                xr[j + Q::VR - 1] = ok ? xr[j + Q::VR - 1] : 0.f;
+            }
+#pragma unroll
+            for (int kw = 0; kw < 3; ++kw)
+#pragma unroll
+                for (int x = 0; x < Q::CW; ++x) acc[x] = fmaf(xr[x * S + kw + Q::VR - 1], w[kh * 3 + kw], acc[x]);
+        }
+    }
+    asm volatile("" ::: "memory");
+    // ---- results to their flat position in the region (every lane has read its window) ----
+    if (active) {
+        float *op = data + r * Q::Wout + qs * Q::CW;
+#pragma unroll
+        for (int e = 0; e < Q::CW; e += Q::VO) {
+            if constexpr (Q::VO == 4) *reinterpret_cast<f32x4 *>(op + e) = f32x4{acc[e], acc[e + 1], acc[e + 2], acc[e + 3]};
+            else if constexpr (Q::VO == 2) *reinterpret_cast<float2 *>(op + e) = float2{acc[e], acc[e + 1]};
+            else op[e] = acc[e];
+        }
+    }
+    asm volatile("" ::: "memory");
+    const __amdgpu_buffer_rsrc_t ry = make_rsrc(p.y, t.y_bytes);
+    const __amdgpu_buffer_rsrc_t rr = make_rsrc(p.res ? p.res : p.y, t.y_bytes);
+    const unsigned obase = (plane * (unsigned)(Q::Hout * Q::Wout) + band * (unsigned)Q::OUT) * 4u;
+#pragma unroll
+    for (int j = 0; j < Q::NSO; ++j) {
+        const int q = lane + 64 * j;
+        if (q * 4 < Q::OUT) {
+            f32x4 v = *reinterpret_cast<const f32x4 *>(data + q * 4);
+            if (p.res) v += __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(rr, obase + q * 16, 0, 0));
+            if (p.relu) v = f32x4{fmaxf(v.x, 0.f), fmaxf(v.y, 0.f), fmaxf(v.z, 0.f), fmaxf(v.w, 0.f)};
+            __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, v), ry, obase + q * 16, 0, 0);
+        }
+    }
+}
+
+template <int I> struct DwBandInst;
+#define GSPC_DW_BAND_INST(I, S_, E_, BR_, NQ_) \
+    template <> struct DwBandInst<I> { using Q = DwBandGeom<S_, E_, E_, BR_, NQ_>; static constexpr int S = S_, E = E_, BR = BR_, NQ = NQ_; }
+// One instance, the only shape where the form measured faster than the strip kernel at N = 256: 112x112 stride 1
+// (168 -> 144 and 316 -> 291 us for 32 and 64 channels).  Within 2 % either way: 112x112 stride 2 in bands of 14 rows;
+// slower: 56x56 in bands of 14 rows (stride 1: 173 against 150 us for whole planes; stride 2: 107 against 100 us for
+// the strip kernel), lanes of 14 instead of 28 outputs on 112x112 (169 us).
+GSPC_DW_BAND_INST(0, 1, 112, 16, 4);
+constexpr int kDwBandInsts = 1;
+
+template <int I = 0>
+bool plan_dw_band(const ConvParams &p, DwPlan *out) {
+    if constexpr (I < kDwBandInsts) {
+        using T = DwBandInst<I>;
+        using Q = typename T::Q;
+        const bool shape = p.stride == T::S && p.H == T::E && p.W == T::E;
+        const double planes = (double)p.N * p.Cin, chunks = planes * Q::NBD;
+        const double xb = planes * (T::E * T::E) * 4, yb = planes * (Q::Hout * Q::Wout) * 4, wb = (double)p.groups * 9 * p.KPGd * 4;
+        const double slack = 4.0 * Q::IN * 4 + 65536;
+        if (!shape || chunks < 4.0 * 2 * kNumCU || chunks >= 4.0e9 || xb + slack >= (double)kOob || yb + slack >= (double)kOob ||
+            wb >= (double)kOob || planes * p.Cin >= 4.29e9)
+            return plan_dw_band<I + 1>(p, out);
+        TileW t{};
+        t.planes = (unsigned)planes;
+        t.chunks = (unsigned)chunks;
+        t.m_C = div_magic(p.Cin);
+        t.x_bytes = (unsigned)xb;
+        t.y_bytes = (unsigned)yb;
+        t.w_bytes = (unsigned)wb;
+        std::memcpy(out->data, &t, sizeof(t));
+        out->data[kDwKind] = 2;
+        out->data[kDwInst] = I;
+        return true;
+    } else {
+        return false;
+    }
+}
+
+template <int I = 0>
+hipError_t launch_dw_band(int inst, const ConvParams &p, const TileW &t, hipStream_t s, const char **name) {
+    if constexpr (I < kDwBandInsts) {
+        if (inst != I) return launch_dw_band<I + 1>(inst, p, t, s, name);
+        using T = DwBandInst<I>;
+        using Q = typename T::Q;
+        *name = intern_name("conv_dw_band<" + std::to_string(T::S) + "," + std::to_string(T::E) + "," + std::to_string(T::E) +
+                            "," + std::to_string(T::BR) + "," + std::to_string(T::NQ) + ">");
+        const size_t lds = (size_t)4 * Q::REGION * sizeof(float);
+        hipLaunchKernelGGL((conv_dw_band<T::S, T::E, T::E, T::BR, T::NQ>), dim3((t.chunks + 3) / 4), dim3(256), lds, s, p, t);
+        return hipGetLastError();
+    } else {
+        return hipErrorNotSupported;
+    }
+}
+
 bool plan_dw_planes(const ConvParams &p, DwPlan *out) {
     static const bool off = std::getenv("GSPC_NO_DWPLANES") != nullptr;   // tuning aid
     if (off || p.CPG != 1 || p.KPG != 1 || p.in_bf16 || p.KH != 3 || p.KW != 3 || p.pad != 1 ||
         (p.stride != 1 && p.stride != 2))
         return false;
     if (plan_dw_wave(p, out)) return true;
+    {
+        static const bool off = std::getenv("GSPC_NO_DWBAND") != nullptr;   // tuning aid
+        if (!off && plan_dw_band(p, out)) return true;
+    }
     out->data[kDwKind] = 0;
     TileD t{};
     t.LWp = p.W + 2;
@@ -505,6 +692,11 @@ inline int dw_row_width(const ConvParams &p) {
 }  // namespace
 
 hipError_t launch_dw_planes(const ConvParams &p, const DwPlan &plan, hipStream_t s, const char **name) {
+    if (plan.data[kDwKind] == 2) {
+        TileW tw;
+        std::memcpy(&tw, plan.data, sizeof(tw));
+        return launch_dw_band(plan.data[kDwInst], p, tw, s, name);
+    }
     if (plan.data[kDwKind] == 1) {
         TileW tw;
         std::memcpy(&tw, plan.data, sizeof(tw));

@@ -146,19 +146,20 @@ def test_depthwise_pairs(gpu):
 
 
 DW_WAVE = [   # (N, C, plane edge, stride): enough planes for the whole-planes-per-wavefront kernel, ragged last wavefront
-    (17, 129, 56, 1), (33, 129, 28, 1), (63, 131, 28, 2), (37, 521, 14, 1), (33, 521, 14, 2), (129, 1031, 7, 1), (129, 1031, 7, 2),
+    (3, 101, 112, 1), (17, 129, 56, 1), (33, 129, 28, 1), (63, 131, 28, 2), (37, 521, 14, 1), (33, 521, 14, 2), (129, 1031, 7, 1), (129, 1031, 7, 2),
 ]
 
 
 @pytest.mark.parametrize("N,C,hw,stride", DW_WAVE, ids=lambda v: str(v))
 def test_depthwise_whole_planes_per_wavefront(gpu, N, C, hw, stride):
-    """Depthwise 3x3 on 28x28, 14x14 and 7x7 planes at batches that fill the chip: whole tensors against the
-    oracle, plane count not a multiple of a wavefront's share; then the same layer with residual and ReLU in a chain."""
+    """Depthwise 3x3 at batches that fill the chip, on 56x56 to 7x7 planes (whole planes per wavefront) and on
+    112x112 planes (a band of rows per wavefront): whole tensors against the oracle, plane count not a
+    multiple of a wavefront's share; then the same layer with residual and ReLU in a chain."""
     torch, b = gpu
     from helpers import gpu_chain, oracle_chain
     s = S(N, C, hw, hw, C, 3, 3, stride, 1, C)
     name = check(gpu, s, seed=wl.make_seed(4, 700 + hw, stride))
-    assert name.startswith(f"conv_dw_wave<{stride},{hw},{hw},"), name
+    assert name.startswith((f"conv_dw_wave<{stride},{hw},{hw},", f"conv_dw_band<{stride},{hw},{hw},")), name
     ho = (hw - 1) // stride + 1
     ch = wl.Chain("dwres", (N, C, hw, hw))
     ch.conv(0, 1, N, C, hw, hw, C, 3, stride, 1, C, relu=True)
@@ -172,7 +173,7 @@ def test_depthwise_whole_planes_per_wavefront(gpu, N, C, hw, stride):
         bf.fill_(float("nan"))
     b.gspc_run_layer_chain(lc)
     torch.cuda.synchronize()
-    assert b.gspc_last_kernel().startswith("conv_dw_wave<"), b.gspc_last_kernel()
+    assert b.gspc_last_kernel().startswith(("conv_dw_wave<", "conv_dw_band<")), b.gspc_last_kernel()
     for i in (1, 2, 3):
         got = bufs[i][:N * C * ho * ho].cpu().numpy().reshape(ref[i].shape)
         assert rel_err(got, ref[i]) < TOL_F32, i
