@@ -59,7 +59,7 @@ def main():
     ap.add_argument("--traffic-probe", action="store_true",
                     help="first run a plain 256 MiB device copy three times: the known-size kernel "
                          "against which rocprofv3's FETCH_SIZE / WRITE_SIZE counters are scaled")
-    ap.add_argument("--sweep", choices=["wrn", "wrn_n256", "resnet_bf16", "depthwise", "blocks", "latency", "winograd", "mobilenetv2"],
+    ap.add_argument("--sweep", choices=["wrn", "wrn_n256", "resnet_bf16", "depthwise", "blocks", "latency", "winograd", "mobilenetv2", "yardstick"],
                     help="instead of the headline step, time every layer of a configuration family "
                          "and print one JSON line with a row per layer")
     ap.add_argument("--fusion", action="store_true",
@@ -103,6 +103,42 @@ def main():
         if args.sweep == "wrn":
             shapes = [s for g in GROUPS for s in wl.wrn_grouped_shapes(BATCH, g)]
             rows = layer_timing.time_layers(shapes, "f32")
+        elif args.sweep == "yardstick":
+            # A yardstick from outside this library, for context only: the vendor library's batched GEMM
+            # (torch.bmm) on each layer's per-group contraction, [g][N*Hout*Wout][CPG*9] x [g][CPG*9][KPG], with the
+            # im2col matrix given to it for free (forming it would move nine times the input).  Same flops as Eq. 2.
+            rows = []
+            legs = [("f32", [s for g in (1, 2, 4) for s in wl.wrn_grouped_shapes(BATCH, g)]),
+                    ("bf16", [s for s in wl.resnet34_grouped_shapes(256, 2)])]
+            b.gspc_set_winograd(0)   # like against like: the direct sum on both sides
+            for dtype, shapes in legs:
+                seen = []
+                for s in shapes:
+                    if s not in seen:
+                        seen.append(s)
+                ours = layer_timing.time_layers(seen, dtype, inner=6, reps=5)
+                for s, r in zip(seen, ours):
+                    ho, wo = b.gspc_output_dims(s.H, s.W, s.KH, s.KW, s.stride, s.pad)
+                    P, K, KPG = s.N * ho * wo, (s.Cin // s.groups) * s.KH * s.KW, s.Cout // s.groups
+                    td = torch.bfloat16 if dtype == "bf16" else torch.float32
+                    A = torch.randn(s.groups, P, K, device=dev, dtype=td)
+                    Bm = torch.randn(s.groups, K, KPG, device=dev, dtype=td)
+                    out = torch.empty(s.groups, P, KPG, device=dev, dtype=td)
+                    for _ in range(3):
+                        torch.bmm(A, Bm, out=out)
+                    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                    torch.cuda.synchronize()
+                    e0.record()
+                    for _ in range(20):
+                        torch.bmm(A, Bm, out=out)
+                    e1.record()
+                    torch.cuda.synchronize()
+                    us = e0.elapsed_time(e1) / 20 * 1e3
+                    rows.append({"layer": r["layer"], "dtype": dtype, "kernel": r["kernel"], "us": r["us"], "tflops": r["tflops"],
+                                 "gemm": f"{s.groups} x [{P} x {K}] x [{K} x {KPG}]", "library_gemm_us": round(us, 2),
+                                 "library_gemm_tflops": round(2.0 * s.groups * P * K * KPG / us / 1e6, 2)})
+                    del A, Bm, out
+            b.gspc_set_winograd(None)
         elif args.sweep == "wrn_n256":
             # the compute-bound layers again at batch 256: steady-state matrix-core efficiency
             shapes = [s for g in (1, 2, 4) for s in wl.wrn_grouped_shapes(256, g) if s.stride == 1]

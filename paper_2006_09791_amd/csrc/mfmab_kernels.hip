@@ -465,7 +465,8 @@ bool planB_cfg(const ConvParams &p, const PackGeom &g, const CfgB &c, TileB *out
 
     t.in_bytes = t.NB * t.IMGB + 8 * t.PPB;
     const size_t wchunk = (size_t)t.wslots * NT * 16;
-    if (t.in_bytes + wchunk > (size_t)kLdsBudgetB) return false;
+    // (64-filter blocks carry 36 KB of filters per chunk: they may fill half a compute unit's LDS)
+    if (t.in_bytes + wchunk > (size_t)(c.MI == 4 ? kLdsResB : kLdsBudgetB)) return false;
     t.wres = t.in_bytes + g.nchunks_b * wchunk <= (size_t)kLdsResB;
     t.nchunks = g.nchunks_b;
     t.mtiles = g.mtiles_b;
@@ -584,9 +585,11 @@ bool plan_mfma_bf16(const ConvParams &p0, const PackGeom &g, MfmaB16Plan *out) {
     long best_blocks = -1;
     TileB bt{};
     // Planes of up to 8 x 8 pixels (several images per tile, so a tile's staging is all halo and index
-    // work): 64 filters per block halve the staging per multiplication (the 512-channel 7x7 layers at
-    // N = 256: 62 -> 46 us for g = 2, 20 -> 18 us for g = 8; on 14 x 14 planes and up it changes nothing).
-    if (forced < 0 && p.H * p.W <= 64) {
+    // work) and stride-2 layers (the staged tile is four times the output tile): 64 filters per block
+    // halve the staging per multiplication (N = 256: the 512-channel 7x7 layers 62 -> 46 us for g = 2 and
+    // 20 -> 18 us for g = 8; 128 -> 256 on 28x28 stride 2 45 -> 41 us, 256 -> 512 on 14x14 stride 2 44 -> 36 us;
+    // on stride-1 planes of 14 x 14 and up it changes nothing).
+    if (forced < 0 && (p.H * p.W <= 64 || p.stride == 2)) {
         TileB t;
         if (planB_cfg(p, g, kCfgB[kNumCfgB - 1], &t) &&
             (long)t.row_blocks * t.img_blocks * t.oc_blocks * p.groups >= 4 * kNumCU) {
