@@ -26,7 +26,7 @@ from . import workloads as wl
 # family letter -> (kernel-name prefix, candidate indices)
 FAMILIES = {
     "w": ("conv_mfma16w<", range(5)),
-    "m": ("conv_mfma16<", range(13)),
+    "m": ("conv_mfma16<", range(14)),
     "b": ("conv_mfma16b<", range(7)),
     "q": ("conv_mfma4r<", (1, 2, 4)),
     "x": ("conv_wino<", range(7)),      # Winograd F(2x2, 3x3): fp32, 3x3, stride 1, pad 1

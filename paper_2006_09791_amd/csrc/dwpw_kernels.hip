@@ -463,8 +463,10 @@ int plan_dwpw(const gspc_layer_t *layers, int first, int count, void *const *buf
 
     // Every filter tile of the pointwise layer recomputes the depthwise tile: fuse only while
     // that is at most two of them (four at stride 2, where a depthwise output costs the same
-    // but the unfused pair moves four times the input per output).  Measured break-even.
-    const int max_ocb = force_ocb ? force_ocb : (A.stride == 2 ? 4 : 2);
+    // but the unfused pair moves four times the input per output).  Measured break-even; from 256
+    // filters on, the dense pointwise layer has its 128-filter blocks and the pair as two kernels is
+    // ahead at stride 2 as well (128 channels -> 256 filters at N = 256: 260 against 276 us).
+    const int max_ocb = force_ocb ? force_ocb : (A.stride == 2 && B.Cout < 256 ? 4 : 2);
     // The largest tile that still gives every compute unit two blocks, else the shape with the
     // most blocks; with less than one block per compute unit the pair is faster as two
     // kernels, whose finer tiles spread over more of the chip (small batches).

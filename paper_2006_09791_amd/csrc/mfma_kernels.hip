@@ -382,9 +382,10 @@ const Cfg16 kCfg16[] = {
     {4, 4, 1, 4, 0}, {2, 4, 1, 4, 0}, {4, 2, 1, 4, 0}, {2, 2, 1, 4, 0}, {1, 4, 1, 4, 0}, {2, 2, 2, 2, 0},
     {1, 2, 1, 4, 0}, {2, 1, 1, 4, 0}, {1, 1, 1, 4, 0},
     {2, 2, 1, 4, 1}, {1, 2, 1, 4, 1}, {2, 1, 1, 4, 1}, {1, 1, 1, 4, 1},
+    {4, 2, 2, 4, 0},   // eight waves, 128 filters x 128 pixels per block: dense pointwise layers (see plan16)
 };
 constexpr int kNumCfg16 = sizeof(kCfg16) / sizeof(kCfg16[0]);
-constexpr int kFirstKsplit = 9;
+constexpr int kFirstKsplit = 9, kEndKsplit = 13;
 
 bool shape_instantiated(int KH, int KW, int S) {
     return (KH == 3 && KW == 3 && (S == 1 || S == 2)) || (KH == 1 && KW == 1 && (S == 1 || S == 2)) ||
@@ -506,7 +507,9 @@ bool plan16(const ConvParams &p, const PackGeom &g, int *cfg_idx, Tile16 *t_out)
     const int forced = force ? std::atoi(force) : tuned_config(p, 'm');
     if (forced >= 0) {
         const int i = forced;
-        if (i >= 0 && i < kNumCfg16 && plan16_cfg(p, g, kCfg16[i], t_out)) {
+        // (eight-wave blocks: two per compute unit, hence 64 KB each)
+        if (i >= 0 && i < kNumCfg16 &&
+            plan16_cfg(p, g, kCfg16[i], t_out, i >= 13 ? 64 * 1024 : kLdsBudget16)) {
             *cfg_idx = i;
             return true;
         }
@@ -528,6 +531,19 @@ bool plan16(const ConvParams &p, const PackGeom &g, int *cfg_idx, Tile16 *t_out)
         if (plan16_cfg(p, g, kCfg16[5], &t) &&
             (long)t.row_blocks * t.img_blocks * t.oc_blocks * p.groups >= 2 * kNumCU) {
             *cfg_idx = 5;
+            *t_out = t;
+            return true;
+        }
+    }
+    // Dense pointwise layers on larger planes: a block of eight waves with 128 filters x 128 pixels reads the input
+    // half as often as the 64-filter shapes (two blocks of 64 KB per compute unit).  At N = 256: 128 -> 256 on 56x56
+    // 800 -> 705 us, 256 -> 512 on 28x28 602 -> 555 us, 512 -> 1024 on 14x14 627 -> 570 us; wider or taller blocks
+    // (128 x 256, 256 x 64) and four-wave blocks of 128 x 128 measured behind it.
+    if (pointwise && p.groups == 1 && p.stride == 1) {
+        Tile16 t;
+        if (plan16_cfg(p, g, kCfg16[kEndKsplit], &t, 64 * 1024) &&
+            (long)t.row_blocks * t.img_blocks * t.oc_blocks >= 2 * kNumCU) {
+            *cfg_idx = kEndKsplit;
             *t_out = t;
             return true;
         }
@@ -574,7 +590,7 @@ bool plan16(const ConvParams &p, const PackGeom &g, int *cfg_idx, Tile16 *t_out)
         int kbest = -1;
         long kblocks = -1;
         Tile16 kt{};
-        for (int i = kFirstKsplit; i < kNumCfg16; ++i) {
+        for (int i = kFirstKsplit; i < kEndKsplit; ++i) {
             Tile16 t;
             if (!plan16_cfg(p, g, kCfg16[i], &t)) continue;
             const long blocks = (long)t.row_blocks * t.img_blocks * t.oc_blocks * p.groups;
@@ -667,6 +683,7 @@ hipError_t launch16_cfg(int i, const ConvParams &p, const Tile16 &t, hipStream_t
     case 10: return launch16_shape<1, 2, 1, 4, TIN>(p, t, s);
     case 11: return launch16_shape<2, 1, 1, 4, TIN>(p, t, s);
     case 12: return launch16_shape<1, 1, 1, 4, TIN>(p, t, s);
+    case 13: return launch16_shape<4, 2, 2, 4, TIN>(p, t, s);
     }
     return hipErrorNotSupported;
 }
