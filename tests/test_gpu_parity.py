@@ -495,3 +495,15 @@ def test_pointwise_on_odd_planes_bf16(gpu):
     _, wr = wl.round_to_bf16(w)
     ref = oracle.conv2d_grouped(xr, wr, 1, 0, 1, threads=8)
     assert rel_err(y, ref) < 1e-4, name
+
+
+# Dense pointwise layers with at least 128 filters at batches that give every compute unit two blocks run in
+# eight-wave blocks of 128 filters x 128 pixels.
+@pytest.mark.parametrize("s", [
+    S(48, 64, 28, 28, 256, 1, 1, 1, 0, 1),     # 784-pixel planes: tiles straddle images
+    S(113, 96, 30, 20, 128, 1, 1, 1, 0, 1),    # ragged last pixel tile, one filter block
+    S(140, 160, 14, 14, 384, 1, 1, 1, 0, 1),   # 14x14 planes (re-pitched to rows of 4), three filter blocks
+], ids=lambda s: "x".join(map(str, s)))
+def test_pointwise_in_128_filter_blocks(gpu, s):
+    name = check(gpu, s, seed=wl.make_seed(7, s.Cin, s.H))
+    assert name.startswith("conv_mfma16<4,2,2,4,1,1,1,f32"), name
