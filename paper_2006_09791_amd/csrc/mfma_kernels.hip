@@ -548,6 +548,21 @@ bool plan16(const ConvParams &p, const PackGeom &g, int *cfg_idx, Tile16 *t_out)
             return true;
         }
     }
+    // 3x3 layers whose staged tile is large for its output - stride 2 (four input pixels per output), planes of
+    // up to 8x8 pixels (several images and their halos per tile): 32 filters x 64 pixels per block restages the
+    // input half as often per multiplication as the 16-filter shapes and won every such layer in the offline
+    // tuner's runs (N = 64 and 256: stride-2 stage entries 7-18 % faster, 512-channel 7x7 layers 14 %).
+    if (p.KH == 3 && p.KW == 3 && (p.stride == 2 || p.H * p.W <= 64)) {
+        for (int i : {7, 6}) {   // 32 x 64, else (16 filters per group) 16 x 128
+            Tile16 t;
+            if (plan16_cfg(p, g, kCfg16[i], &t) &&
+                (long)t.row_blocks * t.img_blocks * t.oc_blocks * p.groups >= 2 * kNumCU) {
+                *cfg_idx = i;
+                *t_out = t;
+                return true;
+            }
+        }
+    }
     for (int i = 0; i < kFirstKsplit; ++i) {
         Tile16 t;
         if (pointwise && (i == 0 || i == 1)) continue;

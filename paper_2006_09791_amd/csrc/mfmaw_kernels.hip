@@ -569,12 +569,12 @@ bool plan_mfma16w(const ConvParams &p, const PackGeom &g, Mfma16wPlan *out) {
         (p.stride != 1 && p.stride != 2) || p.W % 4 || g.CPG % 4 || g.CPGp != g.CPG)
         return false;
     // Findings of the tile-table autotuner for stride-2 layers: the plain 16x16x4 kernel is 6-20 %
-    // faster with at most 8 channels per group and 10-25 % faster at batch 16 and below; at batch 64
+    // faster with at most 16 channels per group and 10-25 % faster at batch 16 and below; at batch 64
     // this kernel wins by up to 30 %; at batch 128 and above it wins (7-17 %, with the larger
-    // stride-2 tiles that eight staging slots allow) from 32 channels per group on and loses
+    // stride-2 tiles that eight staging slots allow) from 64 channels per group on and loses
     // below.  A table can overrule.
     const bool asked = tuned_family(p) == 'w';
-    if (p.stride == 2 && !asked && (g.CPG <= 8 || (p.N >= 128 && g.CPG < 32) || p.N <= 16)) return false;
+    if (p.stride == 2 && !asked && (g.CPG <= 16 || (p.N >= 128 && g.CPG <= 32) || p.N <= 16)) return false;
     static const char *force = std::getenv("GSPC_TILEW");
     const int ckb = g.CPG % 8 == 0 ? 2 : 1;
     int forced = force ? std::atoi(force) : tuned_config(p, 'w');

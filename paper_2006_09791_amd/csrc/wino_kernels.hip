@@ -423,7 +423,10 @@ bool plan_wino(const ConvParams &p, const PackGeom &g, bool must_fill, WinoPlan 
         }
         // the first shape that gives every compute unit two blocks - or one, for short reductions with at
         // most two filter blocks (the offline tuner's picks among the 16x16-pixel layers at batch 64)
-        if (blocks >= 2 * kNumCU || (blocks >= kNumCU && t.oc_blocks <= 2 && t.cblks <= 16)) {
+        // (planes of less than 64 pixels - 7x7: a quarter of the 2x2 output tiles' area lies outside the plane -
+        // need four blocks per unit: at two the plain kernel's 32-filter shape is 14 % ahead, 512 channels at N = 64)
+        const long fill = p.H * p.W < 64 ? 4 * kNumCU : 2 * kNumCU;
+        if (blocks >= fill || (blocks >= kNumCU && t.oc_blocks <= 2 && t.cblks <= 16 && p.H * p.W >= 64)) {
             best = i;
             best_ckb = k;
             best_blocks = blocks;

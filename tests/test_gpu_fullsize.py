@@ -65,9 +65,9 @@ def test_wrn_layers_batch256_fp32(g):
     try:
         for i, s in enumerate(wl.wrn_grouped_shapes(256, g)):
             names.append(_sampled_check(s, wl.make_seed(2, 300 + i, g), False, n_img=3, n_oc=4, tol_same=TOL_F32))
-            # stride-1 layers: the resident-filter kernel; stride-2 layers at this batch: the same from 32
+            # stride-1 layers: the resident-filter kernel; stride-2 layers at this batch: the same from 64
             # channels per group on, else the plain one
-            want_w = s.stride == 1 or s.Cin // g >= 32
+            want_w = s.stride == 1 or s.Cin // g >= 64
             assert ("conv_mfma16w" if want_w else "conv_mfma16<") in names[-1], names[-1]
     finally:
         b.gspc_set_winograd(None)
