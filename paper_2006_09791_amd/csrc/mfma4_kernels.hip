@@ -345,8 +345,21 @@ bool plan_mfma4(const ConvParams &p, const PackGeom &g, Mfma4Plan *out) {
         // heavy filter banks (8 channels x 8 filters per group: 144 MFMAs per pixel run) want
         // the launch spread over more, shorter blocks (autotuner: 10.6 -> 8.9 us at N = 64)
         const long enough = g.Kred * MT >= 144 ? 4L * kNumCU : kNumCU / 2;
-        // several images per block only when the launch is plentiful anyway (large batches)
-        if ((t.NB == 1 && blocks >= enough) || blocks >= 4L * kNumCU) break;
+        // several images per block only when the launch is plentiful anyway (large batches); with the
+        // heavy banks four pixel runs per filter-bank read pay from two blocks per compute unit on
+        // (64 -> 64 on 16x16 in 8 groups at N = 256: 21.0 -> 15.1 us)
+        if ((t.NB == 1 && blocks >= enough) || blocks >= 4L * kNumCU ||
+            (nt == 4 && g.Kred * MT >= 144 && blocks >= 2L * kNumCU))
+            break;
+    }
+    // Stride 2: the staged tile is four times the outputs it feeds, so one pixel run per wave keeps
+    // more blocks resident (8-13 % at N = 64 and 256 on the 56x56 and 32x32 planes).
+    if (forced < 0 && chosen > 1 && p.stride == 2) {
+        Tile4 t;
+        if (plan4_tile(p, g, 1, &t)) {
+            chosen = 1;
+            best = t;
+        }
     }
     if (!chosen) return false;
     // Half the pixel runs per wave when that cuts the plane into tiles with clearly fewer idle lanes
