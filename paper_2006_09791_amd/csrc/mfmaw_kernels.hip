@@ -20,14 +20,15 @@
 //     barrier.
 #include <cstdlib>
 #include <cstring>
+#include <type_traits>
 
 #include "conv_common.h"
 
 namespace gspc {
 
-constexpr int kTmaxW = 4;    // input staging slots (16 bytes per lane each) per chunk (stride 1)
+constexpr int kTmaxW = 4;    // most input staging slots (16 bytes per lane each) per chunk (stride 1)
 constexpr int kTmaxW2 = 8;   // the same for stride 2, whose tiles span twice the input rows at twice the width
-constexpr int kWmaxW = 20;   // weight staging slots (16 bytes per thread each), whole reduction
+constexpr int kWmaxW = 20;   // weight staging slots (16 bytes per thread each) of a 256-thread block, whole reduction
 
 struct Tile16w {
     int NB, TH, IHt;         // images, output rows per wave tile; staged input rows
@@ -36,6 +37,7 @@ struct Tile16w {
     int row_blocks, img_blocks, oc_blocks, wave_tiles, tile_groups;   // tile_groups = ceil(wave_tiles / 4)
     int tpr_log2;            // lanes per staged row (log2), 16 bytes per lane
     int tasks, xslots;       // staged rows per chunk, rows per lane per chunk
+    int xs;                  // staging slots the instance is built for (>= xslots)
     int wslots;              // weight slots in total (the first chunk's count is static)
     int ksteps, mtiles;      // geometry of the packed weight section
     int w_floats, stage_floats;
@@ -54,12 +56,11 @@ __device__ unsigned long long g_phase_w[8 * 4096];
 #define GSPC_STAMPW(i)
 #endif
 
-template <int MI, int NI, int S, int CKB, bool PERSIST, typename TIN>
+template <int MI, int NI, int S, int CKB, bool PERSIST, int XS, typename TIN>
 __global__ __launch_bounds__(256) void conv_mfma16w(ConvParams p, Tile16w t) {
     GSPC_STAMPW(0)
     constexpr int NT = 256, TAPS = 9, CK = 4 * CKB, KCHUNK = CKB * TAPS, ES = (int)sizeof(TIN);
-    constexpr int TMAX = S == 2 ? kTmaxW2 : kTmaxW, WMAX = kWmaxW;
-    constexpr int W0 = (KCHUNK * MI * 16 + NT - 1) / NT;   // weight slots the first chunk needs
+    constexpr int TMAX = XS, WMAX = kWmaxW;
     extern __shared__ f32x4 smem4[];
     float *smem = reinterpret_cast<float *>(smem4);
 
@@ -73,36 +74,35 @@ __global__ __launch_bounds__(256) void conv_mfma16w(ConvParams p, Tile16w t) {
     const __amdgpu_buffer_rsrc_t rx = make_rsrc(p.x, t.x_bytes);
     const __amdgpu_buffer_rsrc_t rw = make_rsrc(p.wm, t.w_bytes);
 
-    // ---- weights: thread tid copies 16-byte unit k*256 + tid of the block's
-    // [k-step][MI][64] array; a slot of 256 units covers 16/MI k-steps.
+    // ---- weights: thread tid copies 16-byte unit k*NT + tid of the block's
+    // [k-step][MI][64] array; a slot of NT units covers NT / (16 MI) k-steps.
     constexpr unsigned kStepsPerSlot = NT / (MI * 16);
     const unsigned wrow = t.mtiles * 64 * 4;   // bytes per k-step of the packed section
     const unsigned wblk = ((j * t.ksteps * t.mtiles + ob * MI) * 64) * 4;
     const unsigned wvoff = (tid / (MI * 16)) * wrow + (tid % (MI * 16)) * 16;
-    // Every slot is always requested (slots past the end get the out-of-range
-    // offset and cost no memory traffic): straight-line issue lets the compiler
-    // count exactly how many loads may stay in flight at each wait.
-    f32x4 pw[WMAX];
-    auto fetch_w = [&](int lo, int hi) __attribute__((always_inline)) {
+    // The weights go straight from global memory into LDS (buffer loads with the LDS modifier: lane l of
+    // a wave-level load writes its 16 bytes at the wave's LDS base + 16 l, which is exactly the
+    // [unit k*NT + tid] order), all of them requested here, before anything else: no registers, no
+    // LDS write instructions, and no memory instruction left in the multiply phase for them.  All
+    // blocks fetch their filters at the same moment and the level-2 cache then delivers about 25
+    // bytes per clock to each compute unit: that stream (1.4 us for 74 KB per block) is what the
+    // time to the barrier is made of, and the index arithmetic below runs while it lasts.  (Letting
+    // later chunks' weights arrive behind a second barrier was measured and is slower: the compiler
+    // has to assume that an LDS read may touch what such a load is still writing and waits for it.)
+    // Slots past the end are skipped (a wave-uniform branch): a load with an out-of-range offset
+    // moves no data but still takes its turn in the memory path.
 #pragma unroll
-        for (int k = 0; k < WMAX; ++k)
-            if (k >= lo && k < hi)
-                pw[k] = __builtin_bit_cast(
-                    f32x4, __builtin_amdgcn_raw_buffer_load_b128(rw, k < t.wslots ? wvoff : kOob,
-                                                                 wblk + k * kStepsPerSlot * wrow, 0));
-    };
-    auto commit_w = [&](int lo, int hi) __attribute__((always_inline)) {
-#pragma unroll
-        for (int k = 0; k < WMAX; ++k)
-            if (k >= lo && k < hi) smem4[k * NT + tid] = pw[k];
-    };
+    for (int k = 0; k < WMAX; ++k)
+        if (k < t.wslots)
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(
+                rw, (__attribute__((address_space(3))) void *)(smem4 + k * NT + wave * 64), 16, wvoff,
+                wblk + k * kStepsPerSlot * wrow, 0, 0);
 
-    fetch_w(0, W0);   // first chunk's weights: nothing else is needed to ask for them
-
-    // ---- private input ring: wave w owns two stages -------------------------
-    // (a stage ends with a 16-byte spare slot that absorbs the writes of idle lanes)
+    // ---- private input ring: every wave owns two stages ----------------------
+    // (a stage ends with a spare 16-byte slot per lane that absorbs the writes of idle lanes and idle
+    // slots: one shared slot would make those writes a 64-way conflict on a single bank)
     float *ring = smem + t.w_floats + wave * (2 * t.stage_floats);
-    const unsigned spare = (t.stage_floats - 4) * 4;   // byte offset of the spare slot in a stage
+    const unsigned spare = (t.stage_floats - 256) * 4 + lane * 16;   // byte offset of the lane's spare slot in a stage
     const int rpp = 64 >> t.tpr_log2;
     const int row0 = lane >> t.tpr_log2, colv = lane & ((1 << t.tpr_log2) - 1);
     // What depends on the lane alone: where a staged row goes in the ring, its
@@ -159,17 +159,16 @@ __global__ __launch_bounds__(256) void conv_mfma16w(ConvParams p, Tile16w t) {
     };
     set_tile(blockIdx.x);
     f32x4 pin0[TMAX], pin1[TMAX];
-    auto fetch_x = [&](int chunk, f32x4 (&pin)[TMAX]) __attribute__((always_inline)) {
-        const unsigned so = chunk * CK * HW * ES;
-        const bool on = chunk < t.nchunks;
+    auto fetch_x = [&](int c, f32x4 (&pin)[TMAX]) __attribute__((always_inline)) {
+        const unsigned so = c * CK * HW * ES;
+        const bool on = c < t.nchunks;
 #pragma unroll
         for (int k = 0; k < TMAX; ++k) pin[k] = buf_load_in<TIN>(rx, on ? xoff[k] : kOob, so, 1);
     };
     auto commit_x = [&](int stage, const f32x4 (&pin)[TMAX]) __attribute__((always_inline)) {
         char *bb = reinterpret_cast<char *>(ring) + (stage ? t.stage_floats * 4 : 0);
 #pragma unroll
-        for (int k = 0; k < TMAX; ++k)
-            if (k < t.xslots) *reinterpret_cast<f32x4 *>(bb + xlds[k]) = pin[k];
+        for (int k = 0; k < TMAX; ++k) *reinterpret_cast<f32x4 *>(bb + xlds[k]) = pin[k];   // idle slots: the spare one
     };
 
     // First and second chunk's input of the first tile (the first chunk's weights are on their way).
@@ -200,30 +199,22 @@ __global__ __launch_bounds__(256) void conv_mfma16w(ConvParams p, Tile16w t) {
     // The reduction of a chunk is a sequence of R = 3*CKB rows (one filter row of
     // one 4-channel block: 3 k-steps).  The operands of row i+1 are read from
     // LDS while row i is multiplied (two register sets), across chunk borders
-    // too, so that with one wave per SIMD the matrix core does not wait for LDS.
-    constexpr int R = 3 * CKB;
+    // too, so that the matrix core does not wait for LDS.
+    constexpr int R = 3 * CKB, KS = 3 * R;
     float opa[2][3][MI], opb[2][3][NI];
-    auto load_row = [&](int ch, int row, float (&a)[3][MI], float (&b)[3][NI]) __attribute__((always_inline)) {
-        const int cb = row / 3, kh = row - 3 * cb;
-        const float *xrow = ring + (ch & 1) * t.stage_floats + cb * 4 * t.PLANE + kh * t.LW;
-        const float *ws = smem + (ch * KCHUNK + row * 3) * (MI * 64) + lane;
-#pragma unroll
-        for (int kw = 0; kw < 3; ++kw) {
-#pragma unroll
-            for (int mi = 0; mi < MI; ++mi) a[kw][mi] = ws[(kw * MI + mi) * 64];
-#pragma unroll
-            for (int ni = 0; ni < NI; ++ni) b[kw][ni] = xrow[base[ni] + kw];
-        }
-    };
-    // One k-step (tap kw of a row) of operands, and of MFMAs.
-    auto load_kw = [&](int ch, int row, int kw, float (&a)[3][MI], float (&b)[3][NI]) __attribute__((always_inline)) {
-        const int cb = row / 3, kh = row - 3 * cb;
-        const float *xrow = ring + (ch & 1) * t.stage_floats + cb * 4 * t.PLANE + kh * t.LW;
-        const float *ws = smem + (ch * KCHUNK + row * 3) * (MI * 64) + lane;
+    // One k-step (tap kw of a row of chunk c) of operands, and of MFMAs.
+    auto load_kw = [&](int c, int row, int kw, float (&a)[3][MI], float (&b)[3][NI]) __attribute__((always_inline)) {
+        const int cb = row / 3, khh = row - 3 * cb;
+        const float *xrow = ring + (c & 1) * t.stage_floats + cb * 4 * t.PLANE + khh * t.LW;
+        const float *ws = smem + (c * KCHUNK + row * 3) * (MI * 64) + lane;
 #pragma unroll
         for (int mi = 0; mi < MI; ++mi) a[kw][mi] = ws[(kw * MI + mi) * 64];
 #pragma unroll
         for (int ni = 0; ni < NI; ++ni) b[kw][ni] = xrow[base[ni] + kw];
+    };
+    auto load_row = [&](int c, int row, float (&a)[3][MI], float (&b)[3][NI]) __attribute__((always_inline)) {
+#pragma unroll
+        for (int kw = 0; kw < 3; ++kw) load_kw(c, row, kw, a, b);
     };
     auto mfma_kw = [&](int kw, const float (&a)[3][MI], const float (&b)[3][NI]) __attribute__((always_inline)) {
 #pragma unroll
@@ -232,104 +223,71 @@ __global__ __launch_bounds__(256) void conv_mfma16w(ConvParams p, Tile16w t) {
             for (int ni = 0; ni < NI; ++ni)
                 acc[mi][ni] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[kw][mi], b[kw][ni], acc[mi][ni], 0, 0, 0);
     };
-    // Row i multiplied while row i+1 (chunk nch, row nrow) is read: the reads of a tap follow that tap's MFMAs, so
-    // they issue while the matrix unit works; a burst of all reads in front of the row's MFMAs left the unit idle
-    // for the time the burst takes to issue, every row.
-    auto step_row = [&](const float (&a)[3][MI], const float (&b)[3][NI], int nch, int nrow, float (&na)[3][MI],
-                        float (&nb)[3][NI]) __attribute__((always_inline)) {
-#pragma unroll
-        for (int kw = 0; kw < 3; ++kw) {
-            mfma_kw(kw, a, b);
-            load_kw(nch, nrow, kw, na, nb);
-            __builtin_amdgcn_sched_barrier(0);
-        }
-    };
-    auto mfma_row = [&](const float (&a)[3][MI], const float (&b)[3][NI]) __attribute__((always_inline)) {
-#pragma unroll
-        for (int kw = 0; kw < 3; ++kw)
-#pragma unroll
-            for (int mi = 0; mi < MI; ++mi)
-#pragma unroll
-                for (int ni = 0; ni < NI; ++ni)
-                    acc[mi][ni] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[kw][mi], b[kw][ni], acc[mi][ni], 0, 0, 0);
-    };
-
-    // ---- first chunk, then the rest of the weights --------------------------
-    commit_w(0, W0);
-    commit_x(0, pin0);
-    __syncthreads();
-    GSPC_STAMPW(2)
-#ifdef GSPC_PHASE_TIMING
-    const unsigned long long clkc0 = __builtin_amdgcn_s_memtime();
-#endif
-    // The other weights are requested while the first chunk is multiplied, one
-    // load per k-step or so: the CU's vector memory path takes 16 cycles per
-    // 16-byte-per-lane load and all four waves share it, so a burst of loads
-    // would hold up the MFMAs queued behind it.
-    {
-        constexpr int STEPS = 3 * R, PER = (WMAX - W0 + STEPS - 1) / STEPS;
-        load_row(0, 0, opa[0], opb[0]);
+    // One chunk (no barriers): chunk c is multiplied out of stage c&1 while chunk c+2 is requested
+    // from global memory into the register set pf and chunk c+1 moves from the register set pc
+    // into the other stage.  Row i is multiplied while row i+1 is read, tap by tap: the reads of a
+    // tap follow that tap's MFMAs, so they issue while the matrix unit works (a burst of all reads
+    // in front of a row's MFMAs left the unit idle for the time the burst takes to issue).  The loads
+    // and the LDS writes are dealt out one per k-step the same way; the writes come before the last
+    // row, whose operand reads already belong to chunk c+1.  Every slot is always requested and always committed (idle slots
+    // and chunks past the end carry zeros into the spare slots or into a stage nobody reads again),
+    // so the body holds no branch and the compiler can tell at every wait which loads are in flight.
+    auto chunk = [&](int c, auto par, auto io, f32x4 (&pf)[TMAX], const f32x4 (&pc)[TMAX], int cstage)
+                     __attribute__((always_inline)) {
+        constexpr int P = decltype(par)::value;
+        constexpr bool IO = decltype(io)::value;
+        const unsigned so = (c + 2) * CK * HW * ES;
+        const bool on = c + 2 < t.nchunks;
+        const int cn = c + 1 < t.nchunks ? c + 1 : c;   // the last chunk's look-ahead re-reads its own first row (unused)
+        char *bb = reinterpret_cast<char *>(ring) + (cstage ? t.stage_floats * 4 : 0);
 #pragma unroll
         for (int i = 0; i < R; ++i) {
 #pragma unroll
             for (int kw = 0; kw < 3; ++kw) {
-                mfma_kw(kw, opa[i & 1], opb[i & 1]);
-                fetch_w(W0 + (i * 3 + kw) * PER, W0 + (i * 3 + kw + 1) * PER);
-                if (i + 1 < R) load_kw(0, i + 1, kw, opa[(i + 1) & 1], opb[(i + 1) & 1]);
+                const int s = i * 3 + kw;
+                mfma_kw(kw, opa[(P + i) & 1], opb[(P + i) & 1]);
+                if (IO) {
+#pragma unroll
+                    for (int k = 0; k < TMAX; ++k) {
+                        const int fs = k < KS ? k : KS - 1;
+                        const int cs = KS - 4 - (TMAX - 1 - k) > 0 ? KS - 4 - (TMAX - 1 - k) : 0;
+                        if (fs == s) pf[k] = buf_load_in<TIN>(rx, on ? xoff[k] : kOob, so, 1);
+                        if (cs == s) *reinterpret_cast<f32x4 *>(bb + xlds[k]) = pc[k];
+                    }
+                }
+                load_kw(i + 1 < R ? c : cn, i + 1 < R ? i + 1 : 0, kw, opa[(P + i + 1) & 1], opb[(P + i + 1) & 1]);
                 __builtin_amdgcn_sched_barrier(0);
             }
         }
-    }
-    fetch_x(2, pin0);
-    GSPC_STAMPW(3)
-#ifdef GSPC_PHASE_TIMING
-    const unsigned long long clkc1 = __builtin_amdgcn_s_memtime() - clkc0;
-#endif
-    commit_w(W0, t.wslots);
+    };
+
+    // ---- the one barrier: weights and every wave's first chunk are in LDS -----
+    // (memory loads return in order: waiting for all of them covers the weights, whose arrival no
+    // register dependence would otherwise make the wave wait for)
+    commit_x(0, pin0);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
+    GSPC_STAMPW(2)
+    GSPC_STAMPW(3)
     GSPC_STAMPW(4)
 #ifdef GSPC_PHASE_TIMING
     const unsigned long long clk0 = __builtin_amdgcn_s_memtime();
 #endif
     constexpr int P1 = R & 1;   // register set that holds row 0 of an odd chunk
-    if (t.nchunks > 1) {
-        commit_x(1, pin1);
-        load_row(1, 0, opa[P1], opb[P1]);
-    }
+    load_row(0, 0, opa[0], opb[0]);
 
-    // Steady state, no barriers: iteration ch multiplies chunk ch out of stage
-    // ch&1; before its last row chunk ch+1 moves registers -> the other stage,
-    // chunk ch+2 is requested from global memory at its start (two register
-    // sets pin0 / pin1).
+    // Chunk pairs (even chunk: pin0 is free, pin1 holds the next one; odd chunk: the other way
+    // round), then a last even chunk with nothing left to request or to commit.
     auto steady = [&]() __attribute__((always_inline)) {
-    for (int ch = 1; ch < t.nchunks; ch += 2) {
-        // odd chunk: pin1 is free (chunk ch is in LDS), pin0 holds chunk ch+1
-        fetch_x(ch + 2, pin1);
-#pragma unroll
-        for (int i = 0; i < R; ++i) {
-            if (i + 1 < R) {
-                step_row(opa[(P1 + i) & 1], opb[(P1 + i) & 1], ch, i + 1, opa[(P1 + i + 1) & 1], opb[(P1 + i + 1) & 1]);
-            } else {
-                if (ch + 1 < t.nchunks) commit_x(0, pin0);
-                __builtin_amdgcn_sched_barrier(0);
-                step_row(opa[(P1 + i) & 1], opb[(P1 + i) & 1], ch + 1, 0, opa[(P1 + i + 1) & 1], opb[(P1 + i + 1) & 1]);
-            }
+        using std::integral_constant;
+        const integral_constant<bool, true> yes{};
+        const integral_constant<bool, false> no{};
+        int c = 0;
+        for (; c + 1 < t.nchunks; c += 2) {
+            chunk(c, integral_constant<int, 0>{}, yes, pin0, pin1, 1);
+            chunk(c + 1, integral_constant<int, P1>{}, yes, pin1, pin0, 0);
         }
-        if (ch + 1 < t.nchunks) {
-            // even chunk: pin0 is free, pin1 holds chunk ch+2
-            fetch_x(ch + 3, pin0);
-#pragma unroll
-            for (int i = 0; i < R; ++i) {
-                if (i + 1 < R) {
-                    step_row(opa[i & 1], opb[i & 1], ch + 1, i + 1, opa[(i + 1) & 1], opb[(i + 1) & 1]);
-                } else {
-                    if (ch + 2 < t.nchunks) commit_x(1, pin1);
-                    __builtin_amdgcn_sched_barrier(0);
-                    step_row(opa[i & 1], opb[i & 1], ch + 2, 0, opa[(i + 1) & 1], opb[(i + 1) & 1]);
-                }
-            }
-        }
-    }
+        if (c < t.nchunks) chunk(c, integral_constant<int, 0>{}, no, pin0, pin1, 1);
     };
     // ---- epilogue: optional residual and ReLU, NCHW store -------------------
     // Register r of tile (mi, ni) is filter 16*(tile row) + 4*(lane/16) + r at
@@ -362,11 +320,10 @@ __global__ __launch_bounds__(256) void conv_mfma16w(ConvParams p, Tile16w t) {
     };
 
     steady();
-    GSPC_STAMPW(5)
 #ifdef GSPC_PHASE_TIMING
     if (threadIdx.x == 0) {
         const unsigned bid = blockIdx.x + blockIdx.y * gridDim.x;
-        if (bid < 4096) g_phase_w[bid * 8 + 7] = ((__builtin_amdgcn_s_memtime() - clk0) & 0xffffffffull) | (clkc1 << 32);
+        if (bid < 4096) g_phase_w[bid * 8 + 7] = (__builtin_amdgcn_s_memtime() - clk0) & 0xffffffffull;
     }
 #endif
 
@@ -374,7 +331,9 @@ __global__ __launch_bounds__(256) void conv_mfma16w(ConvParams p, Tile16w t) {
     // The next tile's first two chunks are requested before the results of the
     // current one are stored, so their latency hides behind the epilogue.
     if (!PERSIST) {   // one tile group per block: the common, latency-bound case, kept lean
+        GSPC_STAMPW(5)
         epilogue(ooff);
+        GSPC_STAMPW(6)
         return;
     }
     for (int tg = blockIdx.x;;) {
@@ -396,18 +355,7 @@ __global__ __launch_bounds__(256) void conv_mfma16w(ConvParams p, Tile16w t) {
 #pragma unroll
             for (int ni = 0; ni < NI; ++ni) acc[mi][ni] = f32x4{0.f, 0.f, 0.f, 0.f};
         commit_x(0, pin0);
-        fetch_x(2, pin0);
         load_row(0, 0, opa[0], opb[0]);
-#pragma unroll
-        for (int i = 0; i < R; ++i) {
-            if (i + 1 < R) {
-                step_row(opa[i & 1], opb[i & 1], 0, i + 1, opa[(i + 1) & 1], opb[(i + 1) & 1]);
-            } else {
-                if (t.nchunks > 1) commit_x(1, pin1);
-                __builtin_amdgcn_sched_barrier(0);
-                step_row(opa[i & 1], opb[i & 1], 1, 0, opa[(i + 1) & 1], opb[(i + 1) & 1]);
-            }
-        }
         steady();
     }
     GSPC_STAMPW(6)
@@ -478,16 +426,17 @@ bool planW_cfg(const ConvParams &p, const PackGeom &g, const CfgW &c, int ckb, T
     const int rpp = 64 >> t.tpr_log2;
     t.tasks = CK * t.NB * t.IHt;
     t.xslots = (t.tasks + rpp - 1) / rpp;
-    if (t.xslots > (p.stride == 2 ? kTmaxW2 : kTmaxW)) return false;
+    const int tmax = p.stride == 2 ? kTmaxW2 : kTmaxW;
+    if (t.xslots > tmax) return false;
+    t.xs = t.xslots <= tmax / 2 ? tmax / 2 : tmax;     // the instances are built for half and for all of the slots
     t.ksteps = g.ksteps;
     t.mtiles = g.mtiles;
     t.nchunks = g.CPG / CK;
     const int units = g.ksteps * c.MI * 16;            // 16-byte units of the block's weights
     t.wslots = (units + 255) / 256;
     if (t.wslots > kWmaxW) return false;
-    if (t.wslots < (ckb * 9 * c.MI * 16 + 255) / 256) return false;
     t.w_floats = t.wslots * 256 * 4;
-    t.stage_floats = CK * t.PLANE + 4;
+    t.stage_floats = CK * t.PLANE + 256;   // tile, then a spare 16-byte slot per lane
     const size_t lds = ((size_t)t.w_floats + 8 * (size_t)t.stage_floats) * sizeof(float);
     if (lds > kLdsMaxW) return false;
     t.row_blocks = (p.Hout + t.TH - 1) / t.TH;
@@ -535,30 +484,42 @@ size_t lds_bytes_w(const Tile16w &t) {
     return ((size_t)t.w_floats + 8 * (size_t)t.stage_floats) * sizeof(float);
 }
 
-template <int MI, int NI, int S, int CKB>
-hipError_t launchW_inst(const ConvParams &p, const Tile16w &t, hipStream_t s) {
-    const size_t lds = lds_bytes_w(t);
-    const long gx = grid_x_w(p, t, lds), gy = (long)p.groups * t.oc_blocks;
-    dim3 grid((unsigned)gx, (unsigned)gy);
-    const bool persist = gx < t.tile_groups;
-    auto kern = persist ? conv_mfma16w<MI, NI, S, CKB, true, float> : conv_mfma16w<MI, NI, S, CKB, false, float>;
+template <int MI, int NI, int S, int CKB, bool PERSIST, int XS>
+hipError_t launchW_kernel(const ConvParams &p, const Tile16w &t, dim3 grid, size_t lds, hipStream_t s) {
+    auto kern = conv_mfma16w<MI, NI, S, CKB, PERSIST, XS, float>;
     if (lds > 64 * 1024) {
-        static thread_local bool raised[2] = {false, false};   // per instantiation and thread
-        if (!raised[persist]) {
+        static thread_local bool raised = false;   // per instantiation and thread
+        if (!raised) {
             hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsMaxW);
             if (e != hipSuccess) return e;
-            raised[persist] = true;
+            raised = true;
         }
     }
     hipLaunchKernelGGL(kern, grid, dim3(256), lds, s, p, t);
     return hipGetLastError();
 }
 
+template <int MI, int NI, int S, int CKB, int XS>
+hipError_t launchW_inst(const ConvParams &p, const Tile16w &t, hipStream_t s) {
+    const size_t lds = lds_bytes_w(t);
+    const long gx = grid_x_w(p, t, lds), gy = (long)p.groups * t.oc_blocks;
+    dim3 grid((unsigned)gx, (unsigned)gy);
+    if (gx < t.tile_groups) return launchW_kernel<MI, NI, S, CKB, true, XS>(p, t, grid, lds, s);
+    return launchW_kernel<MI, NI, S, CKB, false, XS>(p, t, grid, lds, s);
+}
+
+template <int MI, int NI, int S>
+hipError_t launchW_xs(int ckb, const ConvParams &p, const Tile16w &t, hipStream_t s) {
+    constexpr int TM = S == 2 ? kTmaxW2 : kTmaxW;
+    if (t.xs == TM / 2)
+        return ckb == 2 ? launchW_inst<MI, NI, S, 2, TM / 2>(p, t, s) : launchW_inst<MI, NI, S, 1, TM / 2>(p, t, s);
+    return ckb == 2 ? launchW_inst<MI, NI, S, 2, TM>(p, t, s) : launchW_inst<MI, NI, S, 1, TM>(p, t, s);
+}
+
 template <int MI, int NI>
 hipError_t launchW_shape(int stride, int ckb, const ConvParams &p, const Tile16w &t, hipStream_t s) {
-    if (stride == 1) return ckb == 2 ? launchW_inst<MI, NI, 1, 2>(p, t, s) : launchW_inst<MI, NI, 1, 1>(p, t, s);
-    return ckb == 2 ? launchW_inst<MI, NI, 2, 2>(p, t, s) : launchW_inst<MI, NI, 2, 1>(p, t, s);
+    return stride == 1 ? launchW_xs<MI, NI, 1>(ckb, p, t, s) : launchW_xs<MI, NI, 2>(ckb, p, t, s);
 }
 
 }  // namespace
