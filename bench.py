@@ -12,6 +12,8 @@ Also reported on the same line:
                  algorithmic flops (or bytes) per launch over its average
                  launch duration, measured here with events on the launch
                  stream by running each of its layers back to back.
+  roofline_direct - when that kernel instance is the Winograd one: the same object for the
+                 direct-sum instance with the largest share (null otherwise).
   roofline_hbm - the same for the HBM-bound side of the path: the MobileNet-shaped
                  depthwise 3x3 layers at batch 256 over rotating buffers, dominant kernel.
   latency_ms   - batch-1 latency of the WRN-40-2-style and ResNet-34-shaped networks
@@ -46,6 +48,45 @@ def layer_flops_bytes(l):
     if l.src2 >= 0:
         nbytes += out_b          # fused residual read
     return 2 * macs, nbytes
+
+
+def _roofline_object(name, k, kernels):
+    """Roofline object of one kernel instance: its summed algorithmic work over its summed event-timed
+    duration, against the matrix-core peak (compute-bound layers) or the HBM peak."""
+    traffic = None
+    if os.path.exists(TRAFFIC_FILE):
+        try:
+            traffic = json.load(open(TRAFFIC_FILE)).get(name)
+        except Exception:
+            traffic = None
+    if ("mfma" in name or "wino" in name) and k["compute_bound"]:
+        ach = k["flops"] / k["time"] / 1e12
+        roofline = {"bound": "mfma", "achieved": round(ach, 2), "peak": PEAK_F32_MFMA_TFLOPS,
+                    "unit": "TFLOP/s", "frac": round(ach / PEAK_F32_MFMA_TFLOPS, 4)}
+        if "wino" in name:
+            # Eq. 2 counts the multiplications of the direct sum; the Winograd kernel executes 16/36 of them.
+            # `achieved` and `frac` are the executed work against the matrix-core peak (a roofline fraction);
+            # the Eq. 2 rate is an effective figure and is reported as such, without a fraction.
+            roofline["algorithm"] = "winograd F(2x2,3x3): executes 16/36 of the Eq. 2 multiplications"
+            roofline["eq2_effective_tflops"] = round(ach, 2)
+            roofline["achieved"] = round(ach * 16.0 / 36.0, 2)
+            roofline["frac"] = round(ach * 16.0 / 36.0 / PEAK_F32_MFMA_TFLOPS, 4)
+    else:
+        ach = k["bytes"] / k["time"] / 1e9
+        roofline = {"bound": "hbm", "achieved": round(ach, 1), "peak": PEAK_HBM_GBS,
+                    "unit": "GB/s", "frac": round(ach / PEAK_HBM_GBS, 4)}
+    traffic_at = None
+    if os.path.exists(TRAFFIC_FILE):
+        try:
+            traffic_at = json.load(open(TRAFFIC_FILE)).get("_measured_at")
+        except Exception:
+            pass
+    roofline.update({"traffic": traffic, "traffic_measured_at": traffic_at,
+                     "traffic_algorithmic": round(k["bytes"] / k["launches"]),
+                     "kernel": name, "launches_per_step": k["launches"],
+                     "avg_launch_us": round(k["time"] / k["launches"] * 1e6, 2),
+                     "share_of_step": round(k["time"] / sum(v["time"] for v in kernels.values()), 3)})
+    return roofline
 
 
 def main():
@@ -296,7 +337,7 @@ def main():
         per_g[str(g)] = {"ms": round(ms, 4), "gmacs": round(ch.macs() / ms / 1e6, 1)}
 
     # ---- roofline of the dominant kernel ------------------------------------
-    roofline = None
+    roofline, roofline_direct = None, None
     kernels = {}
     if not args.no_roofline:
         b.gspc_set_chain_fusion(0)   # this leg times single layers
@@ -337,41 +378,16 @@ def main():
                 if flops / nbytes > PEAK_F32_MFMA_TFLOPS * 1e3 / PEAK_HBM_GBS:
                     k["compute_bound"] = True
         name, k = max(kernels.items(), key=lambda kv: kv[1]["time"])
-        traffic = None
-        if os.path.exists(TRAFFIC_FILE):
-            try:
-                traffic = json.load(open(TRAFFIC_FILE)).get(name)
-            except Exception:
-                traffic = None
-        if ("mfma" in name or "wino" in name) and k["compute_bound"]:
-            ach = k["flops"] / k["time"] / 1e12
-            roofline = {"bound": "mfma", "achieved": round(ach, 2), "peak": PEAK_F32_MFMA_TFLOPS,
-                        "unit": "TFLOP/s", "frac": round(ach / PEAK_F32_MFMA_TFLOPS, 4)}
-            if "wino" in name:
-                # Eq. 2 counts the multiplications of the direct sum; the Winograd kernel executes 16/36 of them.
-                # `achieved` and `frac` are the executed work against the matrix-core peak (a roofline fraction);
-                # the Eq. 2 rate is an effective figure and is reported as such, without a fraction.
-                roofline["algorithm"] = "winograd F(2x2,3x3): executes 16/36 of the Eq. 2 multiplications"
-                roofline["eq2_effective_tflops"] = round(ach, 2)
-                roofline["achieved"] = round(ach * 16.0 / 36.0, 2)
-                roofline["frac"] = round(ach * 16.0 / 36.0 / PEAK_F32_MFMA_TFLOPS, 4)
-        else:
-            ach = k["bytes"] / k["time"] / 1e9
-            roofline = {"bound": "hbm", "achieved": round(ach, 1), "peak": PEAK_HBM_GBS,
-                        "unit": "GB/s", "frac": round(ach / PEAK_HBM_GBS, 4)}
-        traffic_at = None
-        if os.path.exists(TRAFFIC_FILE):
-            try:
-                traffic_at = json.load(open(TRAFFIC_FILE)).get("_measured_at")
-            except Exception:
-                pass
-        roofline.update({"traffic": traffic, "traffic_measured_at": traffic_at,
-                         "traffic_algorithmic": round(k["bytes"] / k["launches"]),
-                         "kernel": name, "launches_per_step": k["launches"],
-                         "avg_launch_us": round(k["time"] / k["launches"] * 1e6, 2),
-                         "share_of_step": round(k["time"] / sum(v["time"] for v in kernels.values()), 3)})
+        roofline = _roofline_object(name, k, kernels)
         all_flops = sum(v["flops"] for v in kernels.values())
         roofline["winograd_share_of_macs"] = round(sum(v["flops"] for n, v in kernels.items() if "wino" in n) / all_flops, 4)
+        if "wino" in name:
+            # the kernel instance with the largest share of the step is the Winograd one: the direct-sum
+            # instance with the largest share is reported next to it
+            direct = {n: v for n, v in kernels.items() if "wino" not in n}
+            if direct:
+                dn, dk = max(direct.items(), key=lambda kv: kv[1]["time"])
+                roofline_direct = _roofline_object(dn, dk, kernels)
 
     # ---- HBM side: depthwise 3x3 layers at batch 256, rotating buffers ------------
     roofline_hbm, latency = None, None
@@ -497,6 +513,7 @@ def main():
         "per_g": per_g,
         "per_g_monotone": all(per_g[str(a)]["ms"] >= per_g[str(c)]["ms"] * 0.97 for a, c in zip(GROUPS, GROUPS[1:])),
         "roofline": roofline,
+        "roofline_direct": roofline_direct,
         "roofline_hbm": roofline_hbm,
         "latency_ms": latency,
         "cpu_baseline": cpu,

@@ -56,6 +56,15 @@ __device__ unsigned long long g_phase_w[8 * 4096];
 #define GSPC_STAMPW(i)
 #endif
 
+// 64 lanes x 16 bytes from global memory straight into LDS: lane l's bytes land at byte offset dst + 16 l of
+// the dynamic LDS array (dst wave-uniform).  (A device-only function: the host pass does not know that this
+// GPU takes 16 bytes per lane in this instruction, and inside a lambda it would be checked there.)
+__device__ __forceinline__ void load_to_lds16(__amdgpu_buffer_rsrc_t r, f32x4 *lds_base, unsigned dst, unsigned voff,
+                                              unsigned soff) {
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(
+        r, (__attribute__((address_space(3))) void *)(reinterpret_cast<char *>(lds_base) + dst), 16, voff, soff, 0, 0);
+}
+
 template <int MI, int NI, int S, int CKB, bool PERSIST, int XS, typename TIN>
 __global__ __launch_bounds__(256) void conv_mfma16w(ConvParams p, Tile16w t) {
     GSPC_STAMPW(0)
@@ -87,16 +96,17 @@ __global__ __launch_bounds__(256) void conv_mfma16w(ConvParams p, Tile16w t) {
     // blocks fetch their filters at the same moment and the level-2 cache then delivers about 25
     // bytes per clock to each compute unit: that stream (1.4 us for 74 KB per block) is what the
     // time to the barrier is made of, and the index arithmetic below runs while it lasts.  (Letting
-    // later chunks' weights arrive behind a second barrier was measured and is slower: the compiler
-    // has to assume that an LDS read may touch what such a load is still writing and waits for it.)
+    // later chunks' weights arrive behind a second barrier, one load every few k-steps, was measured
+    // and is slower: a wave that finds the memory path full waits with its MFMAs.  The same loads for
+    // the input tiles, into a ring of three or four stages, were measured too: stride-2 layers gained
+    // 8-15 %, stride-1 layers lost 5-7 % - the halo columns then travel as out-of-range lanes, twice
+    // the load count on 8-pixel rows.)
     // Slots past the end are skipped (a wave-uniform branch): a load with an out-of-range offset
     // moves no data but still takes its turn in the memory path.
 #pragma unroll
     for (int k = 0; k < WMAX; ++k)
         if (k < t.wslots)
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(
-                rw, (__attribute__((address_space(3))) void *)(smem4 + k * NT + wave * 64), 16, wvoff,
-                wblk + k * kStepsPerSlot * wrow, 0, 0);
+            load_to_lds16(rw, smem4, (k * NT + wave * 64) * 16, wvoff, wblk + k * kStepsPerSlot * wrow);
 
     // ---- private input ring: every wave owns two stages ----------------------
     // (a stage ends with a spare 16-byte slot per lane that absorbs the writes of idle lanes and idle
