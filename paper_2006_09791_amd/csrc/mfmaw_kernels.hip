@@ -591,7 +591,7 @@ hipError_t launch_mfma16w(const ConvParams &p, const Mfma16wPlan &plan, hipStrea
     const bool persist = grid_x_w(p, t, lds_bytes_w(t)) < t.tile_groups;
     *name = intern_name("conv_mfma16w<" + std::to_string(c.MI) + "," + std::to_string(c.NI) + "," +
                         std::to_string(p.stride) + "," + std::to_string(plan.ckb) + "," +
-                        (persist ? "true" : "false") + ",f32>");
+                        (persist ? "true" : "false") + "," + std::to_string(t.xs) + ",f32>");
     switch (plan.inst) {
     case 0: return launchW_shape<2, 4>(p.stride, plan.ckb, p, t, s);
     case 1: return launchW_shape<2, 2>(p.stride, plan.ckb, p, t, s);
