@@ -18,9 +18,17 @@
 //   registers, so the inverse transform A^T M A needs no exchange between lanes; the
 //   2x2 results go straight to NCHW (output reshape fused away).
 //
+//   Where a wave holds one product tile (16 filters x 16 output tiles), V never goes through LDS
+//   (template argument RT): lane l of the wave needs, as the B operand of the sixteen MFMAs of a
+//   k-step, the sixteen transformed values of channel l/16, tile l%16 - exactly what one 4x4 patch
+//   gives - so every lane reads its own patch from the staged tile and transforms it in registers,
+//   the next k-step's while the current one multiplies.  No V buffer, no LDS writes, one barrier per
+//   chunk (the staged tile is double-buffered).
+//
 // Stride 1, pad 1, fp32, KPG >= 12 (the last filter tile zero-padded), CPG a multiple of 4.
 #include <cstdlib>
 #include <cstring>
+#include <type_traits>
 
 #include "conv_common.h"
 
@@ -36,22 +44,24 @@ struct TileX {
     int cblks, mtiles;       // CPG/4, KPG/16: geometry of the packed section
     int raw_floats;
     int wodd;                // odd plane width: 4-byte stores with a column check
+    int rt;                  // V transformed in registers by the wave that multiplies it (one product tile per wave)
     unsigned m_IHt, m_NB, m_tpi, m_TC, m_rowb, m_ocb;
     unsigned x_bytes, u_bytes, y_bytes;
 };
 
 constexpr int kTmaxX = 4;
 
-template <int MI, int NI, int WM, int WP, int CKB>
+template <int MI, int NI, int WM, int WP, int CKB, bool RT>
 __global__ __launch_bounds__(64 * WM * WP, 2) void conv_wino(ConvParams p, TileX t) {
+    static_assert(!RT || (MI == 1 && NI == 1), "the register transform serves one product tile per wave");
     constexpr int NT = 64 * WM * WP, PT = 16 * NI * WP, VP = PT + 16, MIWM = MI * WM, CK = 4 * CKB;
     constexpr int TMAX = kTmaxX;
     constexpr int CPP = NT / PT;                  // channels transformed per pass of the block
     constexpr int TPASS = (CK + CPP - 1) / CPP;
     extern __shared__ f32x4 smem4[];
-    float *raw = reinterpret_cast<float *>(smem4);   // [CK][PLANE]
+    float *raw = reinterpret_cast<float *>(smem4);   // [CK][PLANE] (RT: two of them)
     float *V = raw + t.raw_floats;                   // [16][CK][VP]; VP = 16 mod 32: conflict-free operand reads
-    const unsigned spare = (t.raw_floats + 16 * CK * VP) * 4;
+    const unsigned spare = RT ? 2 * t.raw_floats * 4 : (t.raw_floats + 16 * CK * VP) * 4;
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -124,10 +134,11 @@ __global__ __launch_bounds__(64 * WM * WP, 2) void conv_wino(ConvParams p, TileX
     // Halo columns left and right of a staged row are never written by the staging: clear them once.
     {
         const int rows = CK * t.NB * t.IHt, right = t.XO + p.W;
-        for (int i = tid; i < rows; i += NT) {
-            const int cimg = fast_div(i, t.m_IHt), r = i - cimg * t.IHt;
+        for (int i = tid; i < (RT ? 2 : 1) * rows; i += NT) {
+            const int b = i >= rows, ii = i - b * rows;
+            const int cimg = fast_div(ii, t.m_IHt), r = ii - cimg * t.IHt;
             const int c = fast_div(cimg, t.m_NB), img = cimg - c * t.NB;
-            float *row = raw + c * t.PLANE + img * t.IMG + r * t.LW;
+            float *row = raw + b * t.raw_floats + c * t.PLANE + img * t.IMG + r * t.LW;
             for (int x = 0; x < t.XO; ++x) row[x] = 0.f;
             for (int x = right; x < t.LW; ++x) row[x] = 0.f;
         }
@@ -141,11 +152,52 @@ __global__ __launch_bounds__(64 * WM * WP, 2) void conv_wino(ConvParams p, TileX
 #pragma unroll
             for (int ni = 0; ni < NI; ++ni) acc[xn][mi][ni] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    const float *vrd = V + (lane >> 4) * VP + wp * NI * 16 + (lane & 15);
-    for (int ch = 0; ch < t.nchunks; ++ch) {
-        fetch_u(ch);   // needed after the transform: its latency passes meanwhile
+    if constexpr (RT) {
+        // ---- register transform: this lane's patch (channel lane/16 of the k-step, tile lane%16 of the wave) ----
+        int pbase_r;
         {
-            char *bb = reinterpret_cast<char *>(raw);
+            const int q = wp * 16 + (lane & 15);
+            const int qq = q < t.P ? q : 0;
+            const int img = fast_div(qq, t.m_tpi), rem = qq - img * t.tpi;
+            const int tr = fast_div(rem, t.m_TC), tc = rem - tr * t.TC;
+            pbase_r = (lane >> 4) * t.PLANE + img * t.IMG + 2 * tr * t.LW + (t.XO - 1) + 2 * tc;
+        }
+        f32x4 ub[2][CKB][4];   // U of this chunk and of the next one
+        float vb[2][16];       // V of this k-step and of the next one
+        float d[4][4], w[4][4];
+        auto fetch_ub = [&](int chunk, f32x4 (&u)[CKB][4]) __attribute__((always_inline)) {
+#pragma unroll
+            for (int cb = 0; cb < CKB; ++cb) {
+                const unsigned mt = ob * MIWM + wm;
+                const unsigned so = (((j * t.cblks + chunk * CKB + cb) * t.mtiles + mt) * 4) * 1024;
+#pragma unroll
+                for (int qd = 0; qd < 4; ++qd)
+                    u[cb][qd] = __builtin_bit_cast(
+                        f32x4, __builtin_amdgcn_raw_buffer_load_b128(ru, lane * 16, so + qd * 1024, 0));
+            }
+        };
+        // B^T d B in sixteen slices, one behind each MFMA of the k-step before: rows of the patch are read in
+        // slices 0-3, the column pass runs in slices 8-11 (by then the reads have returned), the row pass in 12-15.
+        auto slice = [&](int i, const float *src, float (&out)[16]) __attribute__((always_inline)) {
+            if (i < 4) {
+#pragma unroll
+                for (int x = 0; x < 4; ++x) d[i][x] = src[i * t.LW + x];
+            } else if (i >= 8 && i < 12) {
+                const int x = i - 8;
+                w[0][x] = d[0][x] - d[2][x];
+                w[1][x] = d[1][x] + d[2][x];
+                w[2][x] = d[2][x] - d[1][x];
+                w[3][x] = d[1][x] - d[3][x];
+            } else if (i >= 12) {
+                const int xi = i - 12;
+                out[xi * 4 + 0] = w[xi][0] - w[xi][2];
+                out[xi * 4 + 1] = w[xi][1] + w[xi][2];
+                out[xi * 4 + 2] = w[xi][2] - w[xi][1];
+                out[xi * 4 + 3] = w[xi][1] - w[xi][3];
+            }
+        };
+        auto commit_x = [&](int ch) __attribute__((always_inline)) {
+            char *bb = reinterpret_cast<char *>(raw + (ch & 1) * t.raw_floats);
 #pragma unroll
             for (int k = 0; k < TMAX; ++k) {
                 if (k < t.xslots) {
@@ -153,52 +205,120 @@ __global__ __launch_bounds__(64 * WM * WP, 2) void conv_wino(ConvParams p, TileX
                     else *reinterpret_cast<float *>(bb + xlds[k]) = pin[k].x;
                 }
             }
-        }
-        __syncthreads();
-        if (ch + 1 < t.nchunks) fetch_x(ch + 1);
-        // ---- V = B^T d B for (channel, tile) pairs ----
+        };
+        // One chunk.  On entry vb[VB0] holds V of its first k-step, ub[PB] its U, and the input of chunk ch+1 is
+        // on its way into pin.  The sixteen MFMAs of a k-step carry, one slice or one load each: the transform of
+        // the next k-step; the loads of chunk ch+1's U (first k-step) and of chunk ch+2's input (last k-step, after
+        // pin has been committed).  Before the last k-step chunk ch+1 is committed to the other staged tile and the
+        // block meets at its one barrier per chunk, so that the last k-step can already transform chunk ch+1's first
+        // one.  (The other tile was last read before the previous barrier.)
+        auto chunk = [&](int ch, auto par) __attribute__((always_inline)) {
+            constexpr int PB = decltype(par)::value, VB0 = CKB % 2 ? PB : 0;
+            const bool more = ch + 1 < t.nchunks;
+            const float *src = raw + (ch & 1) * t.raw_floats + pbase_r;
+            const float *nxt = raw + ((ch + 1) & 1) * t.raw_floats + pbase_r;
+            const unsigned xso = (ch + 2) * CK * HW * 4;
+            const bool xon = ch + 2 < t.nchunks;
 #pragma unroll
-        for (int k = 0; k < TPASS; ++k) {
-            const int c = tc0 + k * CPP;
-            if (CK % CPP == 0 || c < CK) {
-                const float *d = raw + c * t.PLANE + pbase;
-                float w[4][4];
-#pragma unroll
-                for (int x = 0; x < 4; ++x) {
-                    const float d0 = d[x], d1 = d[t.LW + x], d2 = d[2 * t.LW + x], d3 = d[3 * t.LW + x];
-                    w[0][x] = d0 - d2;
-                    w[1][x] = d1 + d2;
-                    w[2][x] = d2 - d1;
-                    w[3][x] = d1 - d3;
+            for (int cb = 0; cb < CKB; ++cb) {
+                const bool last = cb == CKB - 1;
+                if (last && more) {
+                    commit_x(ch + 1);
+                    __syncthreads();
                 }
-                float *vo = V + c * VP + tq;
+                const float *srcn = last ? nxt : src + (cb + 1) * 4 * t.PLANE;
 #pragma unroll
-                for (int xi = 0; xi < 4; ++xi) {
-                    vo[(xi * 4 + 0) * CK * VP] = w[xi][0] - w[xi][2];
-                    vo[(xi * 4 + 1) * CK * VP] = w[xi][1] + w[xi][2];
-                    vo[(xi * 4 + 2) * CK * VP] = w[xi][2] - w[xi][1];
-                    vo[(xi * 4 + 3) * CK * VP] = w[xi][1] - w[xi][3];
+                for (int xn = 0; xn < 16; ++xn) {
+                    acc[xn][0][0] = __builtin_amdgcn_mfma_f32_16x16x4f32(ub[PB][cb][xn >> 2][xn & 3],
+                                                                       vb[(VB0 + cb) & 1][xn], acc[xn][0][0], 0, 0, 0);
+                    slice(xn, srcn, vb[(VB0 + cb + 1) & 1]);
+                    if (cb == 0 && xn % 2 == 1 && xn / 2 < CKB * 4) {   // U of the next chunk: CKB * 4 loads
+                        const int l = xn / 2, ucb = l / 4, qd = l % 4;
+                        const unsigned mt = ob * MIWM + wm;
+                        const unsigned so = (((j * t.cblks + (ch + 1) * CKB + ucb) * t.mtiles + mt) * 4) * 1024;
+                        ub[PB ^ 1][ucb][qd] = __builtin_bit_cast(
+                            f32x4, __builtin_amdgcn_raw_buffer_load_b128(ru, lane * 16, so + qd * 1024, 0));
+                    }
+                    if (last && xn >= 4 && xn < 4 + TMAX) {             // input of chunk ch+2
+                        const int k = xn - 4;
+                        if (k < t.xslots) pin[k] = buf_load_in<float>(rx, xon ? xoff[k] : kOob, xso, t.vec);
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
                 }
             }
-        }
+        };
+        fetch_ub(0, ub[0]);
+        commit_x(0);
         __syncthreads();
-        // ---- sixteen GEMM steps per 4-channel block ----
+        if (t.nchunks > 1) fetch_x(1);
 #pragma unroll
-        for (int cb = 0; cb < CKB; ++cb)
+        for (int i = 0; i < 16; ++i) slice(i, raw + pbase_r, vb[0]);
+        int ch = 0;
+        for (; ch + 1 < t.nchunks; ch += 2) {
+            chunk(ch, std::integral_constant<int, 0>{});
+            chunk(ch + 1, std::integral_constant<int, 1>{});
+        }
+        if (ch < t.nchunks) chunk(ch, std::integral_constant<int, 0>{});
+    } else {
+        const float *vrd = V + (lane >> 4) * VP + wp * NI * 16 + (lane & 15);
+        for (int ch = 0; ch < t.nchunks; ++ch) {
+            fetch_u(ch);   // needed after the transform: its latency passes meanwhile
+            {
+                char *bb = reinterpret_cast<char *>(raw);
 #pragma unroll
-            for (int xn = 0; xn < 16; ++xn) {
-                float b[NI];
-#pragma unroll
-                for (int ni = 0; ni < NI; ++ni) b[ni] = vrd[(xn * CK + cb * 4) * VP + ni * 16];
-#pragma unroll
-                for (int mi = 0; mi < MI; ++mi)
-#pragma unroll
-                    for (int ni = 0; ni < NI; ++ni)
-                        acc[xn][mi][ni] = __builtin_amdgcn_mfma_f32_16x16x4f32(ua[cb][mi][xn >> 2][xn & 3], b[ni],
-                                                                               acc[xn][mi][ni], 0, 0, 0);
+                for (int k = 0; k < TMAX; ++k) {
+                    if (k < t.xslots) {
+                        if (t.vec) *reinterpret_cast<f32x4 *>(bb + xlds[k]) = pin[k];
+                        else *reinterpret_cast<float *>(bb + xlds[k]) = pin[k].x;
+                    }
+                }
             }
-        // the next chunk's staging writes `raw` (free since the second barrier) and, after
-        // its first barrier, V (every wave is past this loop by then)
+            __syncthreads();
+            if (ch + 1 < t.nchunks) fetch_x(ch + 1);
+            // ---- V = B^T d B for (channel, tile) pairs ----
+#pragma unroll
+            for (int k = 0; k < TPASS; ++k) {
+                const int c = tc0 + k * CPP;
+                if (CK % CPP == 0 || c < CK) {
+                    const float *d = raw + c * t.PLANE + pbase;
+                    float w[4][4];
+#pragma unroll
+                    for (int x = 0; x < 4; ++x) {
+                        const float d0 = d[x], d1 = d[t.LW + x], d2 = d[2 * t.LW + x], d3 = d[3 * t.LW + x];
+                        w[0][x] = d0 - d2;
+                        w[1][x] = d1 + d2;
+                        w[2][x] = d2 - d1;
+                        w[3][x] = d1 - d3;
+                    }
+                    float *vo = V + c * VP + tq;
+#pragma unroll
+                    for (int xi = 0; xi < 4; ++xi) {
+                        vo[(xi * 4 + 0) * CK * VP] = w[xi][0] - w[xi][2];
+                        vo[(xi * 4 + 1) * CK * VP] = w[xi][1] + w[xi][2];
+                        vo[(xi * 4 + 2) * CK * VP] = w[xi][2] - w[xi][1];
+                        vo[(xi * 4 + 3) * CK * VP] = w[xi][1] - w[xi][3];
+                    }
+                }
+            }
+            __syncthreads();
+            // ---- sixteen GEMM steps per 4-channel block ----
+#pragma unroll
+            for (int cb = 0; cb < CKB; ++cb)
+#pragma unroll
+                for (int xn = 0; xn < 16; ++xn) {
+                    float b[NI];
+#pragma unroll
+                    for (int ni = 0; ni < NI; ++ni) b[ni] = vrd[(xn * CK + cb * 4) * VP + ni * 16];
+#pragma unroll
+                    for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+                        for (int ni = 0; ni < NI; ++ni)
+                            acc[xn][mi][ni] = __builtin_amdgcn_mfma_f32_16x16x4f32(ua[cb][mi][xn >> 2][xn & 3], b[ni],
+                                                                                   acc[xn][mi][ni], 0, 0, 0);
+                }
+            // the next chunk's staging writes `raw` (free since the second barrier) and, after
+            // its first barrier, V (every wave is past this loop by then)
+        }
     }
 
     // ---- inverse transform Y = A^T M A, optional residual and ReLU, NCHW stores ----
@@ -275,6 +395,7 @@ __global__ __launch_bounds__(64 * WM * WP, 2) void conv_wino(ConvParams p, TileX
     }
 }
 
+
 // ---------------------------------------------------------------------------
 // Host side.
 // ---------------------------------------------------------------------------
@@ -288,7 +409,23 @@ const CfgX kCfgX[] = {{1, 2, 2, 2}, {2, 1, 2, 2}, {1, 1, 2, 2}, {1, 2, 1, 4}, {1
 constexpr int kNumCfgX = sizeof(kCfgX) / sizeof(kCfgX[0]);
 constexpr int kLdsBudgetX = 64 * 1024;
 
-bool planx_cfg(const ConvParams &p, const PackGeom &g, const CfgX &c, int ckb, TileX *out) {
+// LDS of a block: the staged tile and V, or (register transform) two staged tiles; a spare 16 bytes.
+size_t lds_bytes_x(int raw_floats, int CK, int VP, bool rt) {
+    return ((rt ? 2 * (size_t)raw_floats : (size_t)raw_floats + 16 * CK * VP) + 4) * sizeof(float);
+}
+
+// The register transform is taken where a wave holds one product tile, except for very large launches, where the
+// matrix cores are the bound and the V buffer's single transform is ahead: from sixteen blocks per compute unit on
+// with two waves per tile set (each repeats the transform; 8 % at 32 -> 32 on 32x32, N = 1024), from forty-eight on
+// with one (6 % at 64 -> 64 on 56x56 in 4 groups, N = 256).  Tuning aid: GSPC_WINO_RT=0 / 1.
+bool use_rt(const CfgX &c, long blocks) {
+    static const char *env = std::getenv("GSPC_WINO_RT");
+    if (c.MI != 1 || c.NI != 1) return false;
+    if (env) return std::atoi(env) != 0;
+    return blocks < (c.WM == 1 ? 48L : 16L) * kNumCU;
+}
+
+bool planx_cfg(const ConvParams &p, const PackGeom &g, const CfgX &c, int ckb, bool rt, TileX *out) {
     const int PT = 16 * c.NI * c.WP, NT = 64 * c.WM * c.WP, MIWM = c.MI * c.WM, CK = 4 * ckb, VP = PT + 16;
     TileX t{};
     t.cblks = g.CPG / 4;
@@ -317,10 +454,13 @@ bool planx_cfg(const ConvParams &p, const PackGeom &g, const CfgX &c, int ckb, T
     t.vec = p.W % 4 == 0;
     t.XO = t.vec ? 4 : 1;
     t.LW = round_up(t.XO + p.W + 2, 4);
+    // the tiles of a wave read their patches together; with several tile rows among them (planes of 8x8 and less)
+    // a row pitch of 16 floats would put every tile row on the same banks
+    if (t.TC < 16 && (2 * t.LW) % 32 == 0) t.LW += 4;
     t.IMG = t.IHt * t.LW;
     t.PLANE = round_up(t.NB * t.IMG, 4);
     t.raw_floats = CK * t.PLANE;
-    if (((size_t)t.raw_floats + 16 * CK * VP + 4) * sizeof(float) > (size_t)kLdsBudgetX) return false;
+    if (lds_bytes_x(t.raw_floats, CK, VP, rt) > (size_t)kLdsBudgetX) return false;
     t.nchunks = t.cblks / ckb;
     const int cols = t.vec ? p.W / 4 : p.W;
     while ((1 << t.tpr_log2) < cols) ++t.tpr_log2;
@@ -333,6 +473,7 @@ bool planx_cfg(const ConvParams &p, const PackGeom &g, const CfgX &c, int ckb, T
     t.img_blocks = (p.N + t.NB - 1) / t.NB;
     t.oc_blocks = (t.mtiles + MIWM - 1) / MIWM;
     t.wodd = p.W % 2;
+    t.rt = rt;
     t.m_IHt = div_magic(t.IHt);
     t.m_NB = div_magic(t.NB);
     t.m_tpi = div_magic(t.tpi);
@@ -356,24 +497,30 @@ bool planx_cfg(const ConvParams &p, const PackGeom &g, const CfgX &c, int ckb, T
 }
 
 template <int MI, int NI, int WM, int WP, int CKB>
-hipError_t launchx_inst(const ConvParams &p, const TileX &t, hipStream_t s) {
+hipError_t launchx_inst(const ConvParams &p, const TileX &t, bool rt, hipStream_t s) {
     constexpr int PT = 16 * NI * WP, VP = PT + 16, CK = 4 * CKB;
-    const size_t lds = ((size_t)t.raw_floats + 16 * CK * VP + 4) * sizeof(float);
+    const size_t lds = lds_bytes_x(t.raw_floats, CK, VP, rt);
     dim3 grid(t.row_blocks * t.img_blocks, p.groups * t.oc_blocks);
-    hipLaunchKernelGGL((conv_wino<MI, NI, WM, WP, CKB>), grid, dim3(64 * WM * WP), lds, s, p, t);
+    if constexpr (MI == 1 && NI == 1) {
+        if (rt) {
+            hipLaunchKernelGGL((conv_wino<MI, NI, WM, WP, CKB, true>), grid, dim3(64 * WM * WP), lds, s, p, t);
+            return hipGetLastError();
+        }
+    }
+    hipLaunchKernelGGL((conv_wino<MI, NI, WM, WP, CKB, false>), grid, dim3(64 * WM * WP), lds, s, p, t);
     return hipGetLastError();
 }
 
 template <int CKB>
-hipError_t launchx_cfg(int i, const ConvParams &p, const TileX &t, hipStream_t s) {
+hipError_t launchx_cfg(int i, const ConvParams &p, const TileX &t, bool rt, hipStream_t s) {
     switch (i) {
-    case 0: return launchx_inst<1, 2, 2, 2, CKB>(p, t, s);
-    case 1: return launchx_inst<2, 1, 2, 2, CKB>(p, t, s);
-    case 2: return launchx_inst<1, 1, 2, 2, CKB>(p, t, s);
-    case 3: return launchx_inst<1, 2, 1, 4, CKB>(p, t, s);
-    case 4: return launchx_inst<1, 1, 1, 4, CKB>(p, t, s);
-    case 5: return launchx_inst<1, 1, 1, 2, CKB>(p, t, s);
-    case 6: return launchx_inst<1, 1, 1, 1, CKB>(p, t, s);
+    case 0: return launchx_inst<1, 2, 2, 2, CKB>(p, t, rt, s);
+    case 1: return launchx_inst<2, 1, 2, 2, CKB>(p, t, rt, s);
+    case 2: return launchx_inst<1, 1, 2, 2, CKB>(p, t, rt, s);
+    case 3: return launchx_inst<1, 2, 1, 4, CKB>(p, t, rt, s);
+    case 4: return launchx_inst<1, 1, 1, 4, CKB>(p, t, rt, s);
+    case 5: return launchx_inst<1, 1, 1, 2, CKB>(p, t, rt, s);
+    case 6: return launchx_inst<1, 1, 1, 1, CKB>(p, t, rt, s);
     }
     return hipErrorNotSupported;
 }
@@ -410,11 +557,17 @@ bool plan_wino(const ConvParams &p, const PackGeom &g, bool must_fill, WinoPlan 
         if (must_fill && forced < 0 && filters < (g.KPG < 32 ? g.KPG : 32)) continue;
         TileX t;
         int k = ckb;
-        if (!planx_cfg(p, g, kCfgX[i], k, &t)) {
+        // (the block count does not depend on the form; the staged tile's LDS does)
+        bool rt = use_rt(kCfgX[i], 0);
+        if (!planx_cfg(p, g, kCfgX[i], k, rt, &t)) {
             k = 1;
-            if (ckb == 1 || !planx_cfg(p, g, kCfgX[i], k, &t)) continue;
+            if (ckb == 1 || !planx_cfg(p, g, kCfgX[i], k, rt, &t)) continue;
         }
         const long blocks = (long)t.row_blocks * t.img_blocks * t.oc_blocks * p.groups;
+        if (rt && !use_rt(kCfgX[i], blocks)) {
+            TileX t2;
+            if (planx_cfg(p, g, kCfgX[i], k, false, &t2)) t = t2;
+        }
         if (blocks > best_blocks) {
             best = i;
             best_ckb = k;
@@ -450,9 +603,10 @@ hipError_t launch_wino(const ConvParams &p, const WinoPlan &plan, hipStream_t s,
     TileX t;
     std::memcpy(&t, plan.data, sizeof(t));
     const CfgX &c = kCfgX[plan.inst];
+    const bool rt = t.rt != 0;
     *name = intern_name("conv_wino<" + std::to_string(c.MI) + "," + std::to_string(c.NI) + "," + std::to_string(c.WM) +
-                        "," + std::to_string(c.WP) + "," + std::to_string(plan.ckb) + ">");
-    return plan.ckb == 2 ? launchx_cfg<2>(plan.inst, p, t, s) : launchx_cfg<1>(plan.inst, p, t, s);
+                        "," + std::to_string(c.WP) + "," + std::to_string(plan.ckb) + "," + (rt ? "true" : "false") + ">");
+    return plan.ckb == 2 ? launchx_cfg<2>(plan.inst, p, t, rt, s) : launchx_cfg<1>(plan.inst, p, t, rt, s);
 }
 
 }  // namespace gspc
