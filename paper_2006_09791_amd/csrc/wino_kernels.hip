@@ -81,6 +81,9 @@ __global__ __launch_bounds__(64 * WM * WP, 2) void conv_wino(ConvParams p, TileX
     const int row0 = tid >> t.tpr_log2, colv = tid & ((1 << t.tpr_log2) - 1);
     const int vw = t.vec ? 4 : 1;
     unsigned xoff[TMAX], xlds[TMAX];
+    // (the first chunk's load of a slot is requested as soon as the slot's offset is known: the index
+    // arithmetic of the other slots then runs under its latency)
+    f32x4 pin[TMAX];
 #pragma unroll
     for (int k = 0; k < TMAX; ++k) {
         const int task = row0 + k * rpp;
@@ -90,20 +93,20 @@ __global__ __launch_bounds__(64 * WM * WP, 2) void conv_wino(ConvParams p, TileX
             const int cimg = fast_div(task, t.m_IHt), r = task - cimg * t.IHt;
             const int c = fast_div(cimg, t.m_NB), img = cimg - c * t.NB;
             const int ih = ih0 + r, n = n0 + img;
-            xlds[k] = (c * t.PLANE + img * t.IMG + r * t.LW + t.XO + colv * vw) * 4;
             // rows above and below the image load as zero: the halo rows are rewritten with every chunk
             if (n < p.N && ih >= 0 && ih < p.H)
                 xoff[k] = ((((unsigned)n * p.Cin + j * p.CPG + c) * p.H + ih) * p.W + colv * vw) * 4;
+            xlds[k] = (c * t.PLANE + img * t.IMG + r * t.LW + t.XO + colv * vw) * 4;
         }
+        if (k < t.xslots) pin[k] = buf_load_in<float>(rx, xoff[k], 0, t.vec);
+        __builtin_amdgcn_sched_barrier(0);
     }
-    f32x4 pin[TMAX];
     auto fetch_x = [&](int chunk) __attribute__((always_inline)) {
         const unsigned so = chunk * CK * HW * 4;
 #pragma unroll
         for (int k = 0; k < TMAX; ++k)
             if (k < t.xslots) pin[k] = buf_load_in<float>(rx, xoff[k], so, t.vec);
     };
-    fetch_x(0);
 
     // ---- U operand: [g][cblk][mtile][4][64 lanes] float4, four consecutive (xi, nu) per float4 ----
     f32x4 ua[CKB][MI][4];
