@@ -84,6 +84,19 @@ def test_wrn_layers_batch256_automatic_choice(g):
         assert name.startswith("conv_wino<") == eligible, (s, name)
 
 
+def test_winograd_forms_by_launch_size():
+    """One product tile per wave: V is transformed in registers (last template argument true) up to
+    sixteen blocks per compute unit, through the LDS buffer beyond that; both against the oracle on
+    sampled images and filters."""
+    S = wl.ConvShape
+    small = _sampled_check(S(64, 32, 32, 32, 32, 3, 3, 1, 1, 1), wl.make_seed(2, 500, 1), False, n_img=3, n_oc=4,
+                           tol_same=TOL_F32)
+    assert small.startswith("conv_wino<1,1,") and small.endswith(",true>"), small
+    large = _sampled_check(S(512, 32, 32, 32, 32, 3, 3, 1, 1, 1), wl.make_seed(2, 501, 1), False, n_img=3, n_oc=4,
+                           tol_same=TOL_F32)
+    assert large.startswith("conv_wino<1,1,") and large.endswith(",false>"), large
+
+
 def test_residual_chain_batch256_fp32():
     """Residual and ReLU epilogue of the multi-tile form, whole tensors."""
     import torch
